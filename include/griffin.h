@@ -1,0 +1,158 @@
+/*
+ * griffin.h -- C ABI of the MI355X (gfx950) library for GRIFFIN's feed-forward hot path
+ * (arXiv 2404.01365): prompt-conditioned selection of FF neurons, compaction of the selected
+ * weights, and generation through the pruned gated FF block.
+ *
+ * Conventions common to every entry point
+ *   - Every data pointer is DEVICE memory owned by the caller unless its comment says HOST.
+ *     The library never allocates, frees or synchronises; all work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL is the default stream) and the call returns at once.
+ *   - Arguments are validated on the host before any HIP call; a bad argument returns an error
+ *     code and enqueues nothing.  A failed launch returns GRIFFIN_EHIP; griffin_last_hip_error()
+ *     returns the HIP runtime's text for it.
+ *   - Matrices are NEURON-MAJOR: Wg, W1 and W2 are each [n][d] with row stride `ld` elements,
+ *     row j holding neuron j.  Wg and W1 are the paper's W_g and W_1 (D_FF x D, Section 3);
+ *     W2 is the transpose of the paper's W_2 (D x D_FF), so that the "rows of W_1, W_g and
+ *     columns of W_2" selected in Section 4.2 are the same row j of all three arrays.
+ *   - dtype is the storage type of X, x, y and of all weights and biases (fp32 or bf16).
+ *     Accumulation, activations, Z, the statistic s and the selection run in fp32.
+ *   - d must be a multiple of 8; d, n <= 2^20; ld >= d and a multiple of 8 (16-byte rows).
+ */
+#ifndef GRIFFIN_H
+#define GRIFFIN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GRIFFIN_OK = 0,
+    GRIFFIN_EINVAL = 1,        /* null pointer, negative size, bad enum                     */
+    GRIFFIN_ESHAPE = 2,        /* sizes inconsistent with each other or with the alignment  */
+    GRIFFIN_EWORKSPACE = 3,    /* workspace missing or smaller than the *_workspace_bytes   */
+    GRIFFIN_EUNSUPPORTED = 4,  /* valid request this build has no kernel for                */
+    GRIFFIN_EHIP = 5           /* the HIP runtime refused a launch                          */
+} griffin_status;
+
+/* sigma of Eq. 2 / Eq. 3; the GLU variants named in Section 1 (SwiGLU, GEGLU, ReGLU). */
+typedef enum { GRIFFIN_ACT_SILU = 0, GRIFFIN_ACT_GELU_TANH = 1, GRIFFIN_ACT_RELU = 2 } griffin_act;
+typedef enum { GRIFFIN_F32 = 0, GRIFFIN_BF16 = 1 } griffin_dtype;
+
+#define GRIFFIN_MAX_SEQS 256   /* sequences per griffin_prefill_select call      */
+#define GRIFFIN_MAX_BATCH 64   /* rows per griffin_ff_decode* call               */
+
+/*
+ * One FF block (Section 3, Eq. 1-3), full (n = D_FF) or compressed (n = k, Eq. 4-5).
+ * Wg == NULL selects the non-gated FF_1 of Eq. 2.  bg, b1 ([n]) and b2 ([d]) may be NULL;
+ * b2 is never pruned (Eq. 5).
+ */
+typedef struct {
+    int32_t d;        /* model width D                                  */
+    int32_t n;        /* neurons held: D_FF for a full block, k for a compact one */
+    int32_t dtype;    /* griffin_dtype */
+    int32_t act;      /* griffin_act   */
+    const void *Wg;   /* [n][d] stride ld, or NULL */
+    const void *W1;   /* [n][d] stride ld */
+    const void *W2;   /* [n][d] stride ld (transpose of the paper's W_2) */
+    int64_t ld;       /* row stride of the three matrices, in elements */
+    const void *bg;   /* [n] or NULL */
+    const void *b1;   /* [n] or NULL */
+    const void *b2;   /* [d] or NULL */
+} griffin_layer;
+
+const char *griffin_status_string(int status);
+const char *griffin_last_hip_error(void);   /* text of the last HIP failure on this thread */
+const char *griffin_version(void);
+
+/* k for "keep this fraction of D_FF" (Section 5 quotes FF sparsity = 1 - keep):
+ * floor(keep * d_ff + 0.5) clamped to [1, d_ff]. */
+int32_t griffin_k_from_fraction(int32_t d_ff, double keep);
+
+/*
+ * Prompt phase (Section 4.2, "Prompt Phase Expert Neuron Selection").
+ * For n_seqs prompts packed row-wise in X, computes the FF activations Z = FF_1(X) (Eq. 3,
+ * or Eq. 2 when L->Wg is NULL), scales every token row of Z to unit l2 norm (Section 4.1),
+ * takes the l2 norm of every neuron's column over the tokens of each sequence (Eq. 6) and
+ * returns, per sequence, the indices of the k largest entries of s.  Ties go to the lower
+ * index; indices are ascending.  A token whose activations are all zero adds nothing to s.
+ *
+ *   X               [total_tokens][d], row stride ldx elements, L->dtype
+ *   cu_seqlens_host HOST int32 [n_seqs+1]: cu[0] = 0, non-decreasing, cu[n_seqs] = total_tokens;
+ *                   sequence b owns rows cu[b] .. cu[b+1]-1.  Read before the call returns.
+ *   k               1 <= k <= L->n
+ *   idx_out         [n_seqs][k] int32
+ *   s_out           [n_seqs][L->n] fp32, or NULL
+ *   Z_out           [total_tokens][L->n] fp32 with row stride ldz elements, or NULL (then Z
+ *                   lives in the workspace).  Exposed because the prompt's own output uses the
+ *                   full block (Section 5.1) and needs exactly this Z.
+ *   workspace       at least griffin_prefill_workspace_bytes(L, total_tokens, n_seqs,
+ *                   Z_out != NULL) bytes, 256-byte aligned
+ * An empty sequence (length 0) selects indices 0 .. k-1 and reports s = 0.
+ */
+size_t griffin_prefill_workspace_bytes(const griffin_layer *L, int64_t total_tokens,
+                                       int32_t n_seqs, int32_t have_z_out);
+int griffin_prefill_select(const griffin_layer *L, const void *X, int64_t ldx,
+                           const int32_t *cu_seqlens_host, int32_t n_seqs, int32_t k,
+                           int32_t *idx_out, float *s_out, float *Z_out, int64_t ldz,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Top-k of an arbitrary non-negative score (the selection step of Section 4.2 on its own;
+ * also serves the shared-set statistic of Eq. 7 and static scores).
+ *   scores [n_rows][n] fp32, all >= 0 and finite;  idx_out [n_rows][k] int32 ascending.
+ */
+int griffin_topk(const float *scores, int32_t n_rows, int32_t n, int32_t k, int32_t *idx_out,
+                 void *stream);
+
+/*
+ * Shared selection for a batch (Section 5.3, Eq. 7): s_bar = sum_b s_b / sqrt(S_b).
+ *   s [n_seqs][n] fp32 as written by griffin_prefill_select; cu_seqlens_host as above (HOST);
+ *   sbar_out [n] fp32.  Sequences of length 0 are skipped.
+ */
+int griffin_stat_shared(const float *s, const int32_t *cu_seqlens_host, int32_t n_seqs,
+                        int32_t n, float *sbar_out, void *stream);
+
+/*
+ * Compaction (Section 4.2; Eq. 4-5): C->Wg/W1/W2 row t <- L row idx[t], C->bg/b1 entry t <-
+ * L entry idx[t]; b2 is not touched (the caller passes L->b2 as C->b2).  C describes
+ * caller-allocated device buffers: C->n == k, C->d == L->d, same dtype and act, C->ld >= d.
+ * A matrix or bias that is NULL in L must be NULL in C.  idx [k] int32 device, each in
+ * [0, L->n); the kernel clamps out-of-range entries instead of faulting.
+ */
+int griffin_compact(const griffin_layer *L, const int32_t *idx, int32_t k,
+                    const griffin_layer *C, void *stream);
+
+/*
+ * Generation phase (Section 4.2, "Generation with Expert Neurons"; Eq. 4-5):
+ *   z = sigma(Wg x + bg) * (W1 x + b1),   y = sum_j z_j W2[j][:] + b2
+ * for `batch` independent rows x[b] through the ONE block C (a compact block, or a full one
+ * with n = D_FF, which is Eq. 1).  x, y: [batch][d] contiguous, C->dtype.
+ * workspace >= griffin_decode_workspace_bytes(d, n, batch) bytes, 256-byte aligned.
+ */
+size_t griffin_decode_workspace_bytes(int32_t d, int32_t n, int32_t batch);
+int griffin_ff_decode(const griffin_layer *C, const void *x, void *y, int32_t batch,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Per-sequence expert sets (every sample picks its own neurons, Section 4.2): row b of x goes
+ * through its own compact block Cs[b].  Cs is a HOST array of `batch` HOST structs that must
+ * agree in d, n, dtype, act, ld and in which optional pointers are NULL.
+ */
+int griffin_ff_decode_multi(const griffin_layer *Cs, int32_t batch, const void *x, void *y,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The same without compact copies: row b uses neurons idx[b][0..k-1] of the full block L,
+ * read in place.  idx [batch][k] int32 device (out-of-range entries are clamped).
+ */
+int griffin_ff_decode_indexed(const griffin_layer *L, const int32_t *idx, int32_t k,
+                              int32_t batch, const void *x, void *y, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRIFFIN_H */

@@ -1,0 +1,196 @@
+"""Thin Python binding of libgriffin.so (the C ABI declared in include/griffin.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.
+PyTorch supplies device memory (``tensor.data_ptr()``) and the current stream; nothing here
+computes, and there is no CPU or PyTorch fallback -- if the library is missing the import
+fails.  Function names match the C entry points.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgriffin.so")
+
+OK, EINVAL, ESHAPE, EWORKSPACE, EUNSUPPORTED, EHIP = range(6)
+ACT_SILU, ACT_GELU_TANH, ACT_RELU = 0, 1, 2
+F32, BF16 = 0, 1
+MAX_SEQS, MAX_BATCH = 256, 64
+
+
+class GriffinError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib.griffin_status_string(status).decode()
+        if status == EHIP:
+            msg += " (" + lib.griffin_last_hip_error().decode() + ")"
+        super().__init__("%s: %s [status %d]" % (where, msg, status))
+
+
+class griffin_layer(ctypes.Structure):
+    _fields_ = [
+        ("d", ctypes.c_int32), ("n", ctypes.c_int32), ("dtype", ctypes.c_int32), ("act", ctypes.c_int32),
+        ("Wg", ctypes.c_void_p), ("W1", ctypes.c_void_p), ("W2", ctypes.c_void_p),
+        ("ld", ctypes.c_int64),
+        ("bg", ctypes.c_void_p), ("b1", ctypes.c_void_p), ("b2", ctypes.c_void_p),
+    ]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "%s is missing: build it with `python -m paper_2404_01365_amd.build` "
+            "(there is no fallback path)" % LIB_PATH)
+    return ctypes.CDLL(LIB_PATH)
+
+
+lib = _load()
+
+_vp, _i32, _i64, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+_LP = ctypes.POINTER(griffin_layer)
+_IP = ctypes.POINTER(ctypes.c_int32)
+
+_SIGS = {
+    "griffin_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "griffin_last_hip_error": (ctypes.c_char_p, []),
+    "griffin_version": (ctypes.c_char_p, []),
+    "griffin_k_from_fraction": (_i32, [_i32, ctypes.c_double]),
+    "griffin_prefill_workspace_bytes": (_sz, [_LP, _i64, _i32, _i32]),
+    "griffin_prefill_select": (ctypes.c_int, [_LP, _vp, _i64, _IP, _i32, _i32, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
+    "griffin_topk": (ctypes.c_int, [_vp, _i32, _i32, _i32, _vp, _vp]),
+    "griffin_stat_shared": (ctypes.c_int, [_vp, _IP, _i32, _i32, _vp, _vp]),
+    "griffin_compact": (ctypes.c_int, [_LP, _vp, _i32, _LP, _vp]),
+    "griffin_decode_workspace_bytes": (_sz, [_i32, _i32, _i32]),
+    "griffin_ff_decode": (ctypes.c_int, [_LP, _vp, _vp, _i32, _vp, _sz, _vp]),
+    "griffin_ff_decode_multi": (ctypes.c_int, [_LP, _i32, _vp, _vp, _vp, _sz, _vp]),
+    "griffin_ff_decode_indexed": (ctypes.c_int, [_LP, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
+}
+for _name, (_res, _args) in _SIGS.items():
+    _fn = getattr(lib, _name)
+    _fn.restype = _res
+    _fn.argtypes = _args
+
+EXPORTS = tuple(_SIGS)
+
+
+# ------------------------------------------------------------------ marshalling helpers
+def _ptr(t) -> Optional[int]:
+    """Device (or raw integer) address of a tensor; None stays NULL."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise GriffinError(status, where)
+
+
+def layer(W1, W2, Wg=None, *, act: int, dtype: Optional[int] = None, bg=None, b1=None, b2=None,
+          d: Optional[int] = None, n: Optional[int] = None, ld: Optional[int] = None) -> griffin_layer:
+    """Describe one FF block held in torch tensors ([n][d] neuron-major, contiguous rows)."""
+    import torch
+    if dtype is None:
+        dtype = BF16 if W1.dtype == torch.bfloat16 else F32
+    L = griffin_layer()
+    L.n = W1.shape[0] if n is None else n
+    L.d = W1.shape[1] if d is None else d
+    L.ld = W1.stride(0) if ld is None else ld
+    L.dtype, L.act = dtype, act
+    L.Wg, L.W1, L.W2 = _ptr(Wg), _ptr(W1), _ptr(W2)
+    L.bg, L.b1, L.b2 = _ptr(bg), _ptr(b1), _ptr(b2)
+    # keep the tensors alive as long as the descriptor
+    L._keep = (W1, W2, Wg, bg, b1, b2)
+    return L
+
+
+def _cu_array(cu_seqlens: Sequence[int]):
+    arr = (ctypes.c_int32 * len(cu_seqlens))(*[int(v) for v in cu_seqlens])
+    return arr
+
+
+# ------------------------------------------------------------------ entry points
+def griffin_version() -> str:
+    return lib.griffin_version().decode()
+
+
+def griffin_status_string(status: int) -> str:
+    return lib.griffin_status_string(status).decode()
+
+
+def griffin_k_from_fraction(d_ff: int, keep: float) -> int:
+    return int(lib.griffin_k_from_fraction(d_ff, keep))
+
+
+def griffin_prefill_workspace_bytes(L: griffin_layer, total_tokens: int, n_seqs: int = 1,
+                                    have_z_out: bool = False) -> int:
+    return int(lib.griffin_prefill_workspace_bytes(ctypes.byref(L), total_tokens, n_seqs, int(have_z_out)))
+
+
+def griffin_prefill_select(L: griffin_layer, X, cu_seqlens: Sequence[int], k: int, idx_out, *,
+                           s_out=None, Z_out=None, workspace, ldx: Optional[int] = None,
+                           ldz: Optional[int] = None, stream=None) -> None:
+    n_seqs = len(cu_seqlens) - 1
+    if ldx is None:
+        ldx = X.stride(0) if X is not None and X.dim() == 2 else L.d
+    if ldz is None:
+        ldz = Z_out.stride(0) if Z_out is not None else 0
+    st = lib.griffin_prefill_select(ctypes.byref(L), _ptr(X), ldx, _cu_array(cu_seqlens), n_seqs, k,
+                                    _ptr(idx_out), _ptr(s_out), _ptr(Z_out), ldz,
+                                    _ptr(workspace), _nbytes(workspace), _stream(stream))
+    _check(st, "griffin_prefill_select")
+
+
+def griffin_topk(scores, k: int, idx_out, *, stream=None) -> None:
+    n_rows, n = (1, scores.shape[0]) if scores.dim() == 1 else scores.shape
+    _check(lib.griffin_topk(_ptr(scores), n_rows, n, k, _ptr(idx_out), _stream(stream)), "griffin_topk")
+
+
+def griffin_stat_shared(s, cu_seqlens: Sequence[int], sbar_out, *, stream=None) -> None:
+    n_seqs = len(cu_seqlens) - 1
+    _check(lib.griffin_stat_shared(_ptr(s), _cu_array(cu_seqlens), n_seqs, s.shape[-1], _ptr(sbar_out),
+                                   _stream(stream)), "griffin_stat_shared")
+
+
+def griffin_compact(L: griffin_layer, idx, k: int, C: griffin_layer, *, stream=None) -> None:
+    _check(lib.griffin_compact(ctypes.byref(L), _ptr(idx), k, ctypes.byref(C), _stream(stream)),
+           "griffin_compact")
+
+
+def griffin_decode_workspace_bytes(d: int, n: int, batch: int = 1) -> int:
+    return int(lib.griffin_decode_workspace_bytes(d, n, batch))
+
+
+def griffin_ff_decode(C: griffin_layer, x, y, batch: int = 1, *, workspace, stream=None) -> None:
+    _check(lib.griffin_ff_decode(ctypes.byref(C), _ptr(x), _ptr(y), batch, _ptr(workspace),
+                                 _nbytes(workspace), _stream(stream)), "griffin_ff_decode")
+
+
+def griffin_ff_decode_multi(Cs: Sequence[griffin_layer], x, y, *, workspace, stream=None) -> None:
+    arr = (griffin_layer * len(Cs))(*Cs)
+    _check(lib.griffin_ff_decode_multi(arr, len(Cs), _ptr(x), _ptr(y), _ptr(workspace),
+                                       _nbytes(workspace), _stream(stream)), "griffin_ff_decode_multi")
+
+
+def griffin_ff_decode_indexed(L: griffin_layer, idx, k: int, batch: int, x, y, *, workspace,
+                              stream=None) -> None:
+    _check(lib.griffin_ff_decode_indexed(ctypes.byref(L), _ptr(idx), k, batch, _ptr(x), _ptr(y),
+                                         _ptr(workspace), _nbytes(workspace), _stream(stream)),
+           "griffin_ff_decode_indexed")

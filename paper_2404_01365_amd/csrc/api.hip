@@ -1,0 +1,296 @@
+// C ABI of the library: argument validation (before any HIP call), workspace carving and the
+// order of kernel launches.  No allocation, no synchronisation, no host<->device copies.
+#include <stdio.h>
+#include <string.h>
+
+#include "common.h"
+
+namespace griffin {
+
+static thread_local char g_hip_error[256] = "";
+
+int set_hip_error(hipError_t e, const char *what)
+{
+    snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
+    return GRIFFIN_EHIP;
+}
+
+int check_launch(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? GRIFFIN_OK : set_hip_error(e, what);
+}
+
+static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+static inline bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+constexpr int32_t MAX_DIM = 1 << 20;
+
+// shape/pointer checks common to every entry point that takes a block description
+static int check_layer(const griffin_layer *L)
+{
+    if (!L || !L->W1 || !L->W2)
+        return GRIFFIN_EINVAL;
+    if (L->dtype != GRIFFIN_F32 && L->dtype != GRIFFIN_BF16)
+        return GRIFFIN_EINVAL;
+    if (L->act < GRIFFIN_ACT_SILU || L->act > GRIFFIN_ACT_RELU)
+        return GRIFFIN_EINVAL;
+    if (L->d <= 0 || L->n <= 0)
+        return GRIFFIN_EINVAL;
+    if (L->d > MAX_DIM || L->n > MAX_DIM || L->d % 8 != 0 || L->ld < L->d || L->ld % 8 != 0)
+        return GRIFFIN_ESHAPE;
+    if (!aligned16(L->W1) || !aligned16(L->W2) || !aligned16(L->Wg))
+        return GRIFFIN_ESHAPE;
+    if (!L->Wg && L->bg)
+        return GRIFFIN_EINVAL;
+    return GRIFFIN_OK;
+}
+
+static int fill_seq_table(const int32_t *cu, int32_t n_seqs, SeqTable &t, int64_t *total)
+{
+    if (!cu || n_seqs < 1)
+        return GRIFFIN_EINVAL;
+    if (n_seqs > GRIFFIN_MAX_SEQS)
+        return GRIFFIN_EUNSUPPORTED;
+    if (cu[0] != 0)
+        return GRIFFIN_ESHAPE;
+    for (int b = 0; b < n_seqs; ++b)
+        if (cu[b + 1] < cu[b])
+            return GRIFFIN_ESHAPE;
+    t.n = n_seqs;
+    for (int b = 0; b <= n_seqs; ++b)
+        t.cu[b] = cu[b];
+    for (int b = n_seqs + 1; b <= GRIFFIN_MAX_SEQS; ++b)
+        t.cu[b] = cu[n_seqs];
+    *total = cu[n_seqs];
+    return GRIFFIN_OK;
+}
+
+struct PrefillPlan {
+    size_t off_z, off_rowpart, off_w, off_s2part, off_s, total;
+    int nt, rc;
+};
+
+static PrefillPlan plan_prefill(const griffin_layer &L, int64_t total_tokens, int32_t n_seqs, bool have_z)
+{
+    PrefillPlan pl;
+    pl.nt = ff1_ntiles(L);
+    pl.rc = stat_row_chunks(total_tokens, n_seqs, L.n);
+    size_t off = 0;
+    pl.off_z = off;
+    if (!have_z)
+        off += align256((size_t)total_tokens * L.n * sizeof(float));
+    pl.off_rowpart = off;
+    off += align256((size_t)total_tokens * pl.nt * sizeof(float));
+    pl.off_w = off;
+    off += align256((size_t)total_tokens * sizeof(float));
+    pl.off_s2part = off;
+    off += align256((size_t)n_seqs * pl.rc * L.n * sizeof(float));
+    pl.off_s = off;
+    off += align256((size_t)n_seqs * L.n * sizeof(float));
+    pl.total = off;
+    return pl;
+}
+
+}  // namespace griffin
+
+using namespace griffin;
+
+extern "C" {
+
+const char *griffin_status_string(int status)
+{
+    switch (status) {
+    case GRIFFIN_OK: return "ok";
+    case GRIFFIN_EINVAL: return "invalid argument";
+    case GRIFFIN_ESHAPE: return "inconsistent shape or alignment";
+    case GRIFFIN_EWORKSPACE: return "workspace missing or too small";
+    case GRIFFIN_EUNSUPPORTED: return "unsupported configuration";
+    case GRIFFIN_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+const char *griffin_last_hip_error(void) { return g_hip_error; }
+
+const char *griffin_version(void) { return "griffin-gfx950 0.1"; }
+
+int32_t griffin_k_from_fraction(int32_t d_ff, double keep)
+{
+    if (d_ff < 1)
+        return 0;
+    double v = keep * (double)d_ff + 0.5;
+    int64_t k = v <= 1.0 ? 1 : (int64_t)v;
+    if (k < 1) k = 1;
+    if (k > d_ff) k = d_ff;
+    return (int32_t)k;
+}
+
+size_t griffin_prefill_workspace_bytes(const griffin_layer *L, int64_t total_tokens, int32_t n_seqs,
+                                       int32_t have_z_out)
+{
+    if (check_layer(L) != GRIFFIN_OK || total_tokens < 0 || n_seqs < 1 || n_seqs > GRIFFIN_MAX_SEQS)
+        return 0;
+    return plan_prefill(*L, total_tokens, n_seqs, have_z_out != 0).total;
+}
+
+int griffin_prefill_select(const griffin_layer *L, const void *X, int64_t ldx,
+                           const int32_t *cu_seqlens_host, int32_t n_seqs, int32_t k,
+                           int32_t *idx_out, float *s_out, float *Z_out, int64_t ldz,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_layer(L);
+    if (rc != GRIFFIN_OK)
+        return rc;
+    SeqTable seqs;
+    int64_t total = 0;
+    if ((rc = fill_seq_table(cu_seqlens_host, n_seqs, seqs, &total)) != GRIFFIN_OK)
+        return rc;
+    if (!idx_out || (total > 0 && !X))
+        return GRIFFIN_EINVAL;
+    if (k < 1 || k > L->n)
+        return GRIFFIN_ESHAPE;
+    if (ldx < L->d || ldx % 8 != 0 || !aligned16(X) || total > (int64_t)1 << 30)
+        return GRIFFIN_ESHAPE;
+    if (Z_out && ldz < L->n)
+        return GRIFFIN_ESHAPE;
+    const PrefillPlan pl = plan_prefill(*L, total, n_seqs, Z_out != nullptr);
+    if (!workspace || workspace_bytes < pl.total || ((uintptr_t)workspace & 255))
+        return GRIFFIN_EWORKSPACE;
+
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    float *Z = Z_out ? Z_out : (float *)(ws + pl.off_z);
+    const int64_t zld = Z_out ? ldz : L->n;
+    float *rowpart = (float *)(ws + pl.off_rowpart);
+    float *w = (float *)(ws + pl.off_w);
+    float *s2part = (float *)(ws + pl.off_s2part);
+    float *s = (float *)(ws + pl.off_s);
+
+    int32_t nt = 0;
+    if ((rc = launch_ff1(*L, X, ldx, total, Z, zld, rowpart, &nt, st)) != GRIFFIN_OK)
+        return rc;
+    if ((rc = launch_stat(Z, zld, rowpart, nt, total, L->n, seqs, pl.rc, w, s2part, s, s_out, st)) != GRIFFIN_OK)
+        return rc;
+    return launch_topk(s, n_seqs, L->n, k, idx_out, st);
+}
+
+int griffin_topk(const float *scores, int32_t n_rows, int32_t n, int32_t k, int32_t *idx_out, void *stream)
+{
+    if (!scores || !idx_out || n_rows < 0)
+        return GRIFFIN_EINVAL;
+    if (n < 1 || n > MAX_DIM || k < 1 || k > n)
+        return GRIFFIN_ESHAPE;
+    if (n_rows == 0)
+        return GRIFFIN_OK;
+    return launch_topk(scores, n_rows, n, k, idx_out, (hipStream_t)stream);
+}
+
+int griffin_stat_shared(const float *s, const int32_t *cu_seqlens_host, int32_t n_seqs, int32_t n,
+                        float *sbar_out, void *stream)
+{
+    if (!s || !sbar_out)
+        return GRIFFIN_EINVAL;
+    if (n < 1 || n > MAX_DIM)
+        return GRIFFIN_ESHAPE;
+    SeqTable seqs;
+    int64_t total = 0;
+    int rc = fill_seq_table(cu_seqlens_host, n_seqs, seqs, &total);
+    if (rc != GRIFFIN_OK)
+        return rc;
+    return launch_stat_shared(s, seqs, n, sbar_out, (hipStream_t)stream);
+}
+
+int griffin_compact(const griffin_layer *L, const int32_t *idx, int32_t k, const griffin_layer *C, void *stream)
+{
+    int rc = check_layer(L);
+    if (rc != GRIFFIN_OK)
+        return rc;
+    if ((rc = check_layer(C)) != GRIFFIN_OK)
+        return rc;
+    if (!idx)
+        return GRIFFIN_EINVAL;
+    if (k < 1 || k > L->n || C->n != k || C->d != L->d || C->dtype != L->dtype || C->act != L->act)
+        return GRIFFIN_ESHAPE;
+    if ((L->Wg == nullptr) != (C->Wg == nullptr) || (L->bg == nullptr) != (C->bg == nullptr) ||
+        (L->b1 == nullptr) != (C->b1 == nullptr))
+        return GRIFFIN_EINVAL;
+    return launch_compact(*L, idx, k, *C, (hipStream_t)stream);
+}
+
+size_t griffin_decode_workspace_bytes(int32_t d, int32_t n, int32_t batch)
+{
+    if (d < 1 || n < 1 || batch < 1 || batch > GRIFFIN_MAX_BATCH)
+        return 0;
+    return (size_t)decode_parts(n, batch) * batch * d * sizeof(float);
+}
+
+static int decode_common(const griffin_layer *L0, const griffin_layer *multi, const int32_t *idx, int32_t k,
+                         int32_t batch, const void *x, void *y, void *ws, size_t ws_bytes, void *stream)
+{
+    if (batch < 0 || !x || !y)
+        return GRIFFIN_EINVAL;
+    if (batch > GRIFFIN_MAX_BATCH)
+        return GRIFFIN_EUNSUPPORTED;
+    if (!aligned16(x) || !aligned16(y))
+        return GRIFFIN_ESHAPE;
+    const int32_t n = idx ? k : L0->n;
+    if (!ws || ((uintptr_t)ws & 255) || ws_bytes < griffin_decode_workspace_bytes(L0->d, n, batch ? batch : 1))
+        return GRIFFIN_EWORKSPACE;
+    if (batch == 0)
+        return GRIFFIN_OK;
+    DecodeJob job;
+    job.d = L0->d; job.n = n; job.act = L0->act; job.batch = batch;
+    job.bf16 = L0->dtype == GRIFFIN_BF16;
+    job.ld = L0->ld;
+    job.Wg = L0->Wg; job.W1 = L0->W1; job.W2 = L0->W2; job.bg = L0->bg; job.b1 = L0->b1; job.b2 = L0->b2;
+    job.multi = multi;
+    job.idx = idx; job.n_src = L0->n;
+    job.x = x; job.y = y;
+    job.part = (float *)ws; job.part_bytes = ws_bytes;
+    return launch_decode(job, (hipStream_t)stream);
+}
+
+int griffin_ff_decode(const griffin_layer *C, const void *x, void *y, int32_t batch, void *workspace,
+                      size_t workspace_bytes, void *stream)
+{
+    int rc = check_layer(C);
+    if (rc != GRIFFIN_OK)
+        return rc;
+    return decode_common(C, nullptr, nullptr, 0, batch, x, y, workspace, workspace_bytes, stream);
+}
+
+int griffin_ff_decode_multi(const griffin_layer *Cs, int32_t batch, const void *x, void *y, void *workspace,
+                            size_t workspace_bytes, void *stream)
+{
+    if (!Cs || batch < 1)
+        return GRIFFIN_EINVAL;
+    if (batch > GRIFFIN_MAX_BATCH)
+        return GRIFFIN_EUNSUPPORTED;
+    for (int b = 0; b < batch; ++b) {
+        int rc = check_layer(&Cs[b]);
+        if (rc != GRIFFIN_OK)
+            return rc;
+        const griffin_layer &a = Cs[0], &c = Cs[b];
+        if (c.d != a.d || c.n != a.n || c.dtype != a.dtype || c.act != a.act || c.ld != a.ld ||
+            (c.Wg == nullptr) != (a.Wg == nullptr) || (c.bg == nullptr) != (a.bg == nullptr) ||
+            (c.b1 == nullptr) != (a.b1 == nullptr) || (c.b2 == nullptr) != (a.b2 == nullptr))
+            return GRIFFIN_ESHAPE;
+    }
+    return decode_common(&Cs[0], Cs, nullptr, 0, batch, x, y, workspace, workspace_bytes, stream);
+}
+
+int griffin_ff_decode_indexed(const griffin_layer *L, const int32_t *idx, int32_t k, int32_t batch,
+                              const void *x, void *y, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_layer(L);
+    if (rc != GRIFFIN_OK)
+        return rc;
+    if (!idx)
+        return GRIFFIN_EINVAL;
+    if (k < 1 || k > L->n)
+        return GRIFFIN_ESHAPE;
+    return decode_common(L, nullptr, idx, k, batch, x, y, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"

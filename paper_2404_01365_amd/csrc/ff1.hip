@@ -1,0 +1,324 @@
+// Prompt phase, first half: the FF activations of every prompt token (Section 3, Eq. 3 applied
+// row-wise; Eq. 2 when there is no gate),
+//     Z = sigma(X Wg^T + bg) * (X W1^T + b1),
+// together with one sum-of-squares partial per (token row, column tile) from which the row
+// norms of Section 4.1 are finished elsewhere.
+//
+// bf16: a dense contraction, so it runs on the matrix cores.  One workgroup (4 wavefronts, 2x2)
+// owns a 128-token x 128-neuron tile of BOTH products: the X tile is staged once in LDS and
+// feeds two sets of v_mfma_f32_32x32x16_bf16 accumulators (gate and up), so the epilogue finds
+// g_ij and u_ij in the same lane and applies sigma, the gating product, the store of Z and the
+// row sum-of-squares without another pass.  Global->LDS copies are 16-byte, double-buffered
+// through registers; LDS rows are XOR-swizzled in 16-byte chunks so the ds_read_b128 operand
+// fetches are conflict-free.  Workgroup ids are remapped so that each XCD (ids congruent mod 8
+// land on the same XCD) walks a contiguous range of tiles and reuses W tiles in its own L2.
+//
+// fp32: a plain LDS-tiled FMA kernel (64x64 tile); exists for exactness tests and small cases.
+#include "common.h"
+
+namespace griffin {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;   // one 16-byte chunk (8 bf16)
+
+constexpr int G_BM = 128, G_BN = 128, G_BK = 64;
+constexpr int G_THREADS = 256;
+constexpr int F_BM = 64, F_BN = 64, F_BK = 16;
+
+struct Ff1Params {
+    const void *X, *Wg, *W1, *bg, *b1;
+    float *Z, *rowpart;
+    int64_t ldx, ldw, ldz;
+    int32_t M, F, d, nt, mt;
+};
+
+// ------------------------------------------------------------------------------------ bf16 / MFMA
+template <int ACT, bool GATED>
+__global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
+{
+    // [buffer][row][8 chunks of 16 B], chunk c of row r stored at c ^ (r & 7)
+    __shared__ u32x4 As[2][G_BM * 8];
+    __shared__ u32x4 B1s[2][G_BN * 8];
+    __shared__ u32x4 Bgs[GATED ? 2 : 1][GATED ? G_BN * 8 : 1];
+    __shared__ float rs[2][G_BM];
+
+    // XCD-aware tile order
+    const int nblk = p.mt * p.nt;
+    const int per_xcd = (nblk + 7) / 8;
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= nblk)
+        return;
+    const int tile_n = logical / p.mt, tile_m = logical % p.mt;
+    const int m0 = tile_m * G_BM, n0 = tile_n * G_BN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // global -> register staging: thread covers chunk `lc` of rows lr + 32 p
+    const int lr = tid >> 3, lc = tid & 7;
+    const uint16_t *xa[4], *w1a[4], *wga[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int row = lr + 32 * q;
+        const int gm = min(m0 + row, p.M - 1);
+        const int gn = min(n0 + row, p.F - 1);
+        xa[q] = (const uint16_t *)p.X + (int64_t)gm * p.ldx + lc * 8;
+        w1a[q] = (const uint16_t *)p.W1 + (int64_t)gn * p.ldw + lc * 8;
+        wga[q] = GATED ? (const uint16_t *)p.Wg + (int64_t)gn * p.ldw + lc * 8 : nullptr;
+    }
+    u32x4 ra[4], r1[4], rg[4];
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+// global -> registers for the k-tile starting at k0 (chunks past d read as zero)
+#define FF1_LOAD_TILE(k0)                                                     \
+    {                                                                         \
+        const bool ok_ = (k0) + lc * 8 < p.d;                                 \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q)                         \
+        {                                                                     \
+            ra[q] = ok_ ? *(const u32x4 *)(xa[q] + (k0)) : zero4;             \
+            r1[q] = ok_ ? *(const u32x4 *)(w1a[q] + (k0)) : zero4;            \
+            if (GATED)                                                        \
+                rg[q] = ok_ ? *(const u32x4 *)(wga[q] + (k0)) : zero4;        \
+        }                                                                     \
+    }
+// registers -> LDS buffer `buf`
+#define FF1_STORE_TILE(buf)                                                   \
+    {                                                                         \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q)                         \
+        {                                                                     \
+            const int row_ = lr + 32 * q;                                     \
+            const int slot_ = row_ * 8 + (lc ^ (row_ & 7));                   \
+            As[buf][slot_] = ra[q];                                           \
+            B1s[buf][slot_] = r1[q];                                          \
+            if (GATED)                                                        \
+                Bgs[buf][slot_] = rg[q];                                      \
+        }                                                                     \
+    }
+
+    f32x16 accU[2][2], accG[2][2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                accU[mi][ni][i] = 0.0f;
+                accG[mi][ni][i] = 0.0f;
+            }
+
+    const int KT = (p.d + G_BK - 1) / G_BK;
+    FF1_LOAD_TILE(0)
+    FF1_STORE_TILE(0)
+    __syncthreads();
+
+    const int l31 = lane & 31, lh = lane >> 5, sw = lane & 7;
+    for (int kt = 0; kt < KT; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < KT)
+            FF1_LOAD_TILE((kt + 1) * G_BK)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const int ch = (2 * kk + lh) ^ sw;
+            bf16x8 a[2], b1v[2], bgv[2];
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+                a[mi] = __builtin_bit_cast(bf16x8, As[buf][(wm * 64 + mi * 32 + l31) * 8 + ch]);
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                b1v[ni] = __builtin_bit_cast(bf16x8, B1s[buf][(wn * 64 + ni * 32 + l31) * 8 + ch]);
+                if (GATED)
+                    bgv[ni] = __builtin_bit_cast(bf16x8, Bgs[buf][(wn * 64 + ni * 32 + l31) * 8 + ch]);
+            }
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni) {
+                    accU[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b1v[ni], accU[mi][ni], 0, 0, 0);
+                    if (GATED)
+                        accG[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], bgv[ni], accG[mi][ni], 0, 0, 0);
+                }
+        }
+        if (kt + 1 < KT)
+            FF1_STORE_TILE(buf ^ 1)
+        __syncthreads();
+    }
+
+#undef FF1_LOAD_TILE
+#undef FF1_STORE_TILE
+
+    // epilogue.  Lane holds column (neuron) l31 of each 32x32 tile and rows
+    // (i>>2)*8 + lh*4 + (i&3), i = 0..15.
+    float b1j[2], bgj[2];
+    int col[2];
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) {
+        col[ni] = n0 + wn * 64 + ni * 32 + l31;
+        const int cj = min(col[ni], p.F - 1);
+        b1j[ni] = p.b1 ? bf16_bits_to_f32(((const uint16_t *)p.b1)[cj]) : 0.0f;
+        bgj[ni] = (GATED && p.bg) ? bf16_bits_to_f32(((const uint16_t *)p.bg)[cj]) : 0.0f;
+    }
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int lrow = wm * 64 + mi * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
+            const int grow = m0 + lrow;
+            float sq = 0.0f;
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                const float u = accU[mi][ni][i] + b1j[ni];
+                float z;
+                if (GATED)
+                    z = act_apply_t<ACT>(accG[mi][ni][i] + bgj[ni]) * u;
+                else
+                    z = act_apply_t<ACT>(u);
+                if (col[ni] < p.F) {
+                    sq = fmaf(z, z, sq);
+                    if (grow < p.M)
+                        p.Z[(int64_t)grow * p.ldz + col[ni]] = z;
+                }
+            }
+            // sum over the 32 lanes that share this row
+            sq = row16_sum(sq);
+            sq += __shfl_xor(sq, 16, 64);
+            if (l31 == 0)
+                rs[wn][lrow] = sq;
+        }
+    }
+    __syncthreads();
+    if (tid < G_BM && m0 + tid < p.M)
+        p.rowpart[(int64_t)(m0 + tid) * p.nt + tile_n] = rs[0][tid] + rs[1][tid];
+}
+
+// ------------------------------------------------------------------------------------ fp32 / FMA
+template <bool GATED>
+__global__ __launch_bounds__(256) void ff1_f32_kernel(Ff1Params p, int act)
+{
+    __shared__ float Xs[F_BK][F_BM + 4];
+    __shared__ float W1s[F_BK][F_BN + 4];
+    __shared__ float Wgs[F_BK][F_BN + 4];
+
+    const int tile_n = blockIdx.x, tile_m = blockIdx.y;
+    const int m0 = tile_m * F_BM, n0 = tile_n * F_BN;
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int lrow = tid >> 2, lq = tid & 3;   // staging: row, float4 along k
+
+    const float *xp = (const float *)p.X + (int64_t)min(m0 + lrow, p.M - 1) * p.ldx + lq * 4;
+    const float *w1p = (const float *)p.W1 + (int64_t)min(n0 + lrow, p.F - 1) * p.ldw + lq * 4;
+    const float *wgp = GATED ? (const float *)p.Wg + (int64_t)min(n0 + lrow, p.F - 1) * p.ldw + lq * 4 : nullptr;
+
+    float g[4][4], u[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            g[i][j] = u[i][j] = 0.0f;
+
+    for (int k0 = 0; k0 < p.d; k0 += F_BK) {
+        const bool ok = k0 + lq * 4 < p.d;   // d is a multiple of 4
+        float4 vx = ok ? *(const float4 *)(xp + k0) : make_float4(0, 0, 0, 0);
+        float4 v1 = ok ? *(const float4 *)(w1p + k0) : make_float4(0, 0, 0, 0);
+        float4 vg = (GATED && ok) ? *(const float4 *)(wgp + k0) : make_float4(0, 0, 0, 0);
+        __syncthreads();
+        Xs[lq * 4 + 0][lrow] = vx.x; Xs[lq * 4 + 1][lrow] = vx.y; Xs[lq * 4 + 2][lrow] = vx.z; Xs[lq * 4 + 3][lrow] = vx.w;
+        W1s[lq * 4 + 0][lrow] = v1.x; W1s[lq * 4 + 1][lrow] = v1.y; W1s[lq * 4 + 2][lrow] = v1.z; W1s[lq * 4 + 3][lrow] = v1.w;
+        if (GATED) {
+            Wgs[lq * 4 + 0][lrow] = vg.x; Wgs[lq * 4 + 1][lrow] = vg.y; Wgs[lq * 4 + 2][lrow] = vg.z; Wgs[lq * 4 + 3][lrow] = vg.w;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < F_BK; ++kk) {
+            float a[4], b1v[4], bgv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                a[i] = Xs[kk][ty * 4 + i];
+                b1v[i] = W1s[kk][tx * 4 + i];
+                bgv[i] = GATED ? Wgs[kk][tx * 4 + i] : 0.0f;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    u[i][j] = fmaf(a[i], b1v[j], u[i][j]);
+                    if (GATED)
+                        g[i][j] = fmaf(a[i], bgv[j], g[i][j]);
+                }
+        }
+    }
+
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int grow = m0 + ty * 4 + i;
+        float sq = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int colj = n0 + tx * 4 + j;
+            if (colj < p.F) {
+                float uu = u[i][j] + (p.b1 ? ((const float *)p.b1)[colj] : 0.0f);
+                float z;
+                if (GATED)
+                    z = act_apply(act, g[i][j] + (p.bg ? ((const float *)p.bg)[colj] : 0.0f)) * uu;
+                else
+                    z = act_apply(act, uu);
+                sq = fmaf(z, z, sq);
+                if (grow < p.M)
+                    p.Z[(int64_t)grow * p.ldz + colj] = z;
+            }
+        }
+        // the 16 threads that share a row are one DPP row of the wavefront
+        sq = row16_sum(sq);
+        if (tx == 0 && grow < p.M)
+            p.rowpart[(int64_t)grow * p.nt + tile_n] = sq;
+    }
+}
+
+int ff1_ntiles(const griffin_layer &L)
+{
+    const int bn = L.dtype == GRIFFIN_BF16 ? G_BN : F_BN;
+    return (L.n + bn - 1) / bn;
+}
+
+template <int ACT>
+static void launch_mfma(const Ff1Params &p, bool gated, hipStream_t st)
+{
+    const int nblk = p.mt * p.nt;
+    dim3 grid(((nblk + 7) / 8) * 8), block(G_THREADS);
+    if (gated)
+        hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, true>), grid, block, 0, st, p);
+    else
+        hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, false>), grid, block, 0, st, p);
+}
+
+int launch_ff1(const griffin_layer &L, const void *X, int64_t ldx, int64_t M, float *Z, int64_t ldz,
+               float *rowpart, int32_t *nt_out, hipStream_t st)
+{
+    Ff1Params p;
+    p.X = X; p.Wg = L.Wg; p.W1 = L.W1; p.bg = L.bg; p.b1 = L.b1;
+    p.Z = Z; p.rowpart = rowpart;
+    p.ldx = ldx; p.ldw = L.ld; p.ldz = ldz;
+    p.M = (int32_t)M; p.F = L.n; p.d = L.d;
+    p.nt = ff1_ntiles(L);
+    *nt_out = p.nt;
+    if (M == 0)
+        return GRIFFIN_OK;
+    const bool gated = L.Wg != nullptr;
+    if (L.dtype == GRIFFIN_BF16) {
+        p.mt = (int32_t)((M + G_BM - 1) / G_BM);
+        switch (L.act) {
+        case GRIFFIN_ACT_SILU: launch_mfma<GRIFFIN_ACT_SILU>(p, gated, st); break;
+        case GRIFFIN_ACT_GELU_TANH: launch_mfma<GRIFFIN_ACT_GELU_TANH>(p, gated, st); break;
+        default: launch_mfma<GRIFFIN_ACT_RELU>(p, gated, st); break;
+        }
+        return check_launch("ff1_bf16_mfma_kernel");
+    }
+    p.mt = (int32_t)((M + F_BM - 1) / F_BM);
+    dim3 grid(p.nt, p.mt), block(256);
+    if (gated)
+        hipLaunchKernelGGL(ff1_f32_kernel<true>, grid, block, 0, st, p, L.act);
+    else
+        hipLaunchKernelGGL(ff1_f32_kernel<false>, grid, block, 0, st, p, L.act);
+    return check_launch("ff1_f32_kernel");
+}
+
+}  // namespace griffin

@@ -1,0 +1,128 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching the HIP runtime."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2404_01365_amd as G
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000001000  # never dereferenced on these paths (16- and 256-byte aligned)
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "griffin.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(griffin_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    names = declared_functions()
+    assert "griffin_prefill_select" in names and "griffin_compact" in names and "griffin_ff_decode" in names
+    for name in names:
+        assert hasattr(G.lib, name), name
+    assert set(names) == set(G.EXPORTS)
+
+
+def test_struct_layout_matches_header():
+    # 4 x int32, 3 pointers, int64, 3 pointers
+    assert ctypes.sizeof(G.griffin_layer) == 16 + 24 + 8 + 24
+    assert G.griffin_layer.ld.offset == 40 and G.griffin_layer.b2.offset == 64
+
+
+def test_status_strings_and_version():
+    assert G.griffin_status_string(G.OK) == "ok"
+    assert "workspace" in G.griffin_status_string(G.EWORKSPACE)
+    assert G.griffin_status_string(99) == "unknown status"
+    assert "gfx950" in G.griffin_version()
+
+
+def test_k_from_fraction():
+    assert G.griffin_k_from_fraction(11008, 0.5) == 5504
+    assert G.griffin_k_from_fraction(24576, 0.25) == 6144
+    assert G.griffin_k_from_fraction(24576, 0.75) == 18432
+    assert G.griffin_k_from_fraction(10, 0.0) == 1
+    assert G.griffin_k_from_fraction(10, 2.0) == 10
+    assert G.griffin_k_from_fraction(7, 0.5) == 4     # 3.5 rounds half up
+
+
+def mk(d=256, n=688, dtype=G.F32, act=G.ACT_SILU, ld=None, Wg=FAKE, W1=FAKE, W2=FAKE, bg=None):
+    L = G.griffin_layer()
+    L.d, L.n, L.dtype, L.act = d, n, dtype, act
+    L.Wg, L.W1, L.W2, L.ld = Wg, W1, W2, d if ld is None else ld
+    L.bg = bg
+    return L
+
+
+def prefill(L, cu, k, X=FAKE, idx=FAKE, ws=FAKE, ws_bytes=1 << 40, ldx=None, Z=None, ldz=0):
+    arr = (ctypes.c_int32 * len(cu))(*cu) if cu is not None else None
+    return G.lib.griffin_prefill_select(ctypes.byref(L), X, L.d if ldx is None else ldx, arr,
+                                        (len(cu) - 1) if cu is not None else 1, k, idx, None, Z, ldz,
+                                        ws, ws_bytes, None)
+
+
+def test_prefill_rejects_bad_arguments_without_hip():
+    L = mk()
+    assert prefill(mk(W1=None), [0, 64], 344) == G.EINVAL
+    assert prefill(mk(dtype=7), [0, 64], 344) == G.EINVAL
+    assert prefill(mk(act=3), [0, 64], 344) == G.EINVAL
+    assert prefill(mk(d=250), [0, 64], 344) == G.ESHAPE          # d not a multiple of 8
+    assert prefill(mk(ld=128), [0, 64], 344) == G.ESHAPE         # ld < d
+    assert prefill(mk(W1=FAKE + 4), [0, 64], 344) == G.ESHAPE    # misaligned rows
+    assert prefill(mk(Wg=None, bg=FAKE), [0, 64], 344) == G.EINVAL
+    assert prefill(L, [0, 64], 0) == G.ESHAPE
+    assert prefill(L, [0, 64], 689) == G.ESHAPE
+    assert prefill(L, [1, 64], 344) == G.ESHAPE                  # cu[0] != 0
+    assert prefill(L, [0, 64, 32], 344) == G.ESHAPE              # decreasing
+    assert prefill(L, None, 344) == G.EINVAL
+    assert prefill(L, [0, 64], 344, idx=None) == G.EINVAL
+    assert prefill(L, [0, 64], 344, X=None) == G.EINVAL
+    assert prefill(L, [0, 64], 344, ldx=100) == G.ESHAPE
+    assert prefill(L, [0, 64], 344, Z=FAKE, ldz=10) == G.ESHAPE
+    assert prefill(L, [0, 64], 344, ws=None) == G.EWORKSPACE
+    assert prefill(L, [0, 64], 344, ws_bytes=16) == G.EWORKSPACE
+    assert prefill(L, [0, 64], 344, ws=FAKE + 16) == G.EWORKSPACE  # not 256-byte aligned
+    assert prefill(L, [0] * (G.MAX_SEQS + 2), 344) == G.EUNSUPPORTED
+
+
+def test_workspace_queries():
+    L = mk(d=4096, n=11008, dtype=G.BF16)
+    full = G.griffin_prefill_workspace_bytes(L, 512, 1, False)
+    lean = G.griffin_prefill_workspace_bytes(L, 512, 1, True)
+    assert full - lean == 512 * 11008 * 4          # Z lives in the workspace unless Z_out is given
+    assert lean > 0 and lean % 256 == 0
+    assert G.griffin_prefill_workspace_bytes(mk(d=250), 512, 1, False) == 0
+    assert G.griffin_decode_workspace_bytes(4096, 5504, 1) == 256 * 4096 * 4
+    assert G.griffin_decode_workspace_bytes(4096, 5504, 0) == 0
+    assert G.griffin_decode_workspace_bytes(4096, 5504, G.MAX_BATCH + 1) == 0
+
+
+def test_compact_and_decode_reject_bad_arguments_without_hip():
+    L = mk()
+    C = mk(n=344)
+    lib = G.lib
+    assert lib.griffin_compact(ctypes.byref(L), None, 344, ctypes.byref(C), None) == G.EINVAL
+    assert lib.griffin_compact(ctypes.byref(L), FAKE, 343, ctypes.byref(C), None) == G.ESHAPE
+    assert lib.griffin_compact(ctypes.byref(L), FAKE, 344, ctypes.byref(mk(n=344, d=128)), None) == G.ESHAPE
+    assert lib.griffin_compact(ctypes.byref(L), FAKE, 344, ctypes.byref(mk(n=344, Wg=None)), None) == G.EINVAL
+    assert lib.griffin_compact(None, FAKE, 344, ctypes.byref(C), None) == G.EINVAL
+
+    assert lib.griffin_ff_decode(ctypes.byref(C), None, FAKE, 1, FAKE, 1 << 30, None) == G.EINVAL
+    assert lib.griffin_ff_decode(ctypes.byref(C), FAKE, FAKE, 1, None, 0, None) == G.EWORKSPACE
+    assert lib.griffin_ff_decode(ctypes.byref(C), FAKE, FAKE, 1, FAKE, 8, None) == G.EWORKSPACE
+    assert lib.griffin_ff_decode(ctypes.byref(C), FAKE, FAKE, G.MAX_BATCH + 1, FAKE, 1 << 40, None) == G.EUNSUPPORTED
+    assert lib.griffin_ff_decode(ctypes.byref(C), FAKE + 2, FAKE, 1, FAKE, 1 << 30, None) == G.ESHAPE
+    assert lib.griffin_ff_decode(ctypes.byref(C), FAKE, FAKE, 0, FAKE, 1 << 30, None) == G.OK   # nothing to do
+    assert lib.griffin_ff_decode_indexed(ctypes.byref(L), None, 344, 1, FAKE, FAKE, FAKE, 1 << 30, None) == G.EINVAL
+    assert lib.griffin_ff_decode_indexed(ctypes.byref(L), FAKE, 689, 1, FAKE, FAKE, FAKE, 1 << 30, None) == G.ESHAPE
+    two = (G.griffin_layer * 2)(mk(n=344), mk(n=300))
+    assert lib.griffin_ff_decode_multi(two, 2, FAKE, FAKE, FAKE, 1 << 30, None) == G.ESHAPE
+    assert lib.griffin_ff_decode_multi(None, 2, FAKE, FAKE, FAKE, 1 << 30, None) == G.EINVAL
+
+    assert lib.griffin_topk(None, 1, 10, 3, FAKE, None) == G.EINVAL
+    assert lib.griffin_topk(FAKE, 1, 10, 11, FAKE, None) == G.ESHAPE
+    assert lib.griffin_topk(FAKE, 0, 10, 3, FAKE, None) == G.OK
+    cu = (ctypes.c_int32 * 2)(0, 5)
+    assert lib.griffin_stat_shared(None, cu, 1, 10, FAKE, None) == G.EINVAL
