@@ -39,6 +39,10 @@ class griffin_layer(ctypes.Structure):
 
 
 def _load() -> ctypes.CDLL:
+    # libgriffin.so needs libamdhip64.so.7.  PyTorch ships its own copy of that runtime; a
+    # process must not end up with two HIP runtimes (the second one sees no device), so
+    # PyTorch's is loaded first and the dynamic loader hands the same object to libgriffin.
+    import torch  # noqa: F401
     if not os.path.exists(LIB_PATH):
         raise ImportError(
             "%s is missing: build it with `python -m paper_2404_01365_amd.build` "

@@ -1,0 +1,251 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element, on
+seeded inputs small enough for the oracle to finish in seconds but spanning several tiles
+and ragged tails.  Tolerances (max error over the oracle's inf-norm): outputs 1e-5 for fp32
+and 2e-2 for bf16; indices bit-exact on inputs whose top-k margin was opened to > 1e-3.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2404_01365_amd as G
+import synth
+from devio import dev_layer, empty_compact, max_rel, round_like, to_dev, to_host, workspace
+from margin import boundary_report, open_margin
+
+pytestmark = pytest.mark.gpu
+
+TOL_OUT = {synth.DT_F32: 1e-5, synth.DT_BF16: 2e-2}
+# Z and s are fp32 on the device whatever the storage type; products of bf16 inputs are exact
+# in fp32, so only the accumulation order and the fast exp differ from the oracle.
+TOL_Z = 2e-5
+TOL_S = 2e-5
+
+
+def sync():
+    torch.cuda.synchronize()
+
+
+def run_prefill(L, X_dev, cu, k, want_z=True):
+    n_seqs = len(cu) - 1
+    total = int(cu[-1])
+    idx = torch.full((n_seqs, k), -1, dtype=torch.int32, device="cuda")
+    s = torch.full((n_seqs, L.n), -1.0, dtype=torch.float32, device="cuda")
+    Z = torch.full((max(total, 1), L.n), float("nan"), dtype=torch.float32, device="cuda") if want_z else None
+    ws = workspace(G.griffin_prefill_workspace_bytes(L, total, n_seqs, want_z))
+    G.griffin_prefill_select(L, X_dev, [int(v) for v in cu], k, idx, s_out=s, Z_out=Z, workspace=ws)
+    sync()
+    return idx.cpu().numpy(), s.cpu().numpy().astype(np.float64), (None if Z is None else Z.cpu().numpy().astype(np.float64))
+
+
+def run_decode(C, x_dev, batch=1):
+    y = torch.empty_like(x_dev)
+    ws = workspace(G.griffin_decode_workspace_bytes(C.d, C.n, batch))
+    G.griffin_ff_decode(C, x_dev, y, batch, workspace=ws)
+    sync()
+    return to_host(y)
+
+
+# ------------------------------------------------------------------ decode (full block = Eq. 1)
+@pytest.mark.parametrize("dtype,d,n,act,gated,bias", [
+    (synth.DT_F32, 256, 688, synth.ACT_SILU, True, False),        # config-0 shape
+    (synth.DT_F32, 264, 77, synth.ACT_GELU_TANH, True, True),     # ragged chunks, few neurons
+    (synth.DT_F32, 40, 9, synth.ACT_RELU, False, True),           # Eq. 2, fewer neurons than waves
+    (synth.DT_BF16, 512, 1000, synth.ACT_SILU, True, False),
+    (synth.DT_BF16, 520, 333, synth.ACT_GELU_TANH, True, True),   # ragged lanes
+    (synth.DT_BF16, 3072, 257, synth.ACT_RELU, True, False),
+    (synth.DT_BF16, 5120, 130, synth.ACT_SILU, False, True),      # widest register tiling in use
+    (synth.DT_BF16, 6144, 64, synth.ACT_SILU, True, False),
+])
+def test_ff_decode_matches_oracle(dtype, d, n, act, gated, bias):
+    c = synth.small_case(d * 7 + n, d, n, 4, dtype, T=3, with_bias=bias)
+    Wg = c["Wg"] if gated else None
+    bg = c.get("bg") if gated else None
+    L, _ = dev_layer(Wg, c["W1"], c["W2"], act, dtype, bg, c.get("b1"), c.get("b2"))
+    for t in range(3):
+        ref = oracle.ff_decode(c["xt"][t], Wg, c["W1"], c["W2"], act, bg, c.get("b1"), c.get("b2"))
+        got = run_decode(L, to_dev(c["xt"][t], dtype))
+        assert max_rel(got, ref) <= TOL_OUT[dtype], (dtype, d, n, t)
+
+
+def test_ff_decode_batch_rows_are_independent():
+    dtype, d, n = synth.DT_BF16, 1024, 300
+    c = synth.small_case(5, d, n, 4, dtype, T=5)
+    L, _ = dev_layer(c["Wg"], c["W1"], c["W2"], synth.ACT_SILU, dtype)
+    x = to_dev(c["xt"], dtype)
+    got = run_decode(L, x, batch=5)
+    for t in range(5):
+        ref = oracle.ff_decode(c["xt"][t], c["Wg"], c["W1"], c["W2"], synth.ACT_SILU)
+        assert max_rel(got[t], ref) <= TOL_OUT[dtype]
+    # deterministic: a second run gives the same bits
+    assert np.array_equal(got, run_decode(L, x, batch=5))
+
+
+# ------------------------------------------------------------------ compaction
+@pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
+def test_compact_is_a_bit_exact_row_gather(dtype):
+    d, n, k = 264, 301, 97
+    c = synth.small_case(11, d, n, 4, dtype, with_bias=True)
+    L, t = dev_layer(c["Wg"], c["W1"], c["W2"], synth.ACT_SILU, dtype, c["bg"], c["b1"], c["b2"])
+    idx = np.sort(np.random.default_rng(3).choice(n, k, replace=False)).astype(np.int32)
+    C, ct = empty_compact(L, k, t)
+    G.griffin_compact(L, torch.from_numpy(idx).cuda(), k, C)
+    sync()
+    for name in ("Wg", "W1", "W2", "bg", "b1"):
+        assert np.array_equal(to_host(ct[name]), oracle.compact(c[name], idx)), name
+    # pruned decode through the compact block = oracle on the oracle's compact weights
+    x = c["xt"][0]
+    ref = oracle.ff_decode(x, *(oracle.compact(c[m], idx) for m in ("Wg", "W1", "W2")), synth.ACT_SILU,
+                           oracle.compact(c["bg"], idx), oracle.compact(c["b1"], idx), c["b2"])
+    assert max_rel(run_decode(C, to_dev(x, dtype)), ref) <= TOL_OUT[dtype]
+
+
+def test_keep_all_equals_full_block_bitwise_on_device():
+    dtype, d, n = synth.DT_BF16, 512, 200
+    c = synth.small_case(12, d, n, 4, dtype)
+    L, t = dev_layer(c["Wg"], c["W1"], c["W2"], synth.ACT_SILU, dtype)
+    C, _ = empty_compact(L, n, t)
+    G.griffin_compact(L, torch.arange(n, dtype=torch.int32, device="cuda"), n, C)
+    x = to_dev(c["xt"][0], dtype)
+    assert np.array_equal(run_decode(L, x), run_decode(C, x))
+
+
+def test_indexed_and_multi_decode_match_compact_decode():
+    dtype, d, n, k, B = synth.DT_BF16, 1024, 500, 250, 3
+    c = synth.small_case(13, d, n, 4, dtype, T=B, with_bias=True)
+    L, t = dev_layer(c["Wg"], c["W1"], c["W2"], synth.ACT_GELU_TANH, dtype, c["bg"], c["b1"], c["b2"])
+    rng = np.random.default_rng(4)
+    idx = np.stack([np.sort(rng.choice(n, k, replace=False)) for _ in range(B)]).astype(np.int32)
+    idx_dev = torch.from_numpy(idx).cuda()
+    x = to_dev(c["xt"], dtype)
+    refs = []
+    for b in range(B):
+        cw = [oracle.compact(c[m], idx[b]) for m in ("Wg", "W1", "W2")]
+        refs.append(oracle.ff_decode(c["xt"][b], *cw, synth.ACT_GELU_TANH, oracle.compact(c["bg"], idx[b]),
+                                     oracle.compact(c["b1"], idx[b]), c["b2"]))
+    ws = workspace(G.griffin_decode_workspace_bytes(d, k, B))
+    y = torch.empty_like(x)
+    G.griffin_ff_decode_indexed(L, idx_dev, k, B, x, y, workspace=ws)
+    sync()
+    y_idx = to_host(y)
+    Cs, keep = [], []
+    for b in range(B):
+        C, ct = empty_compact(L, k, t)
+        G.griffin_compact(L, idx_dev[b], k, C)
+        Cs.append(C); keep.append(ct)
+    y2 = torch.empty_like(x)
+    G.griffin_ff_decode_multi(Cs, x, y2, workspace=ws)
+    sync()
+    y_multi = to_host(y2)
+    for b in range(B):
+        assert max_rel(y_idx[b], refs[b]) <= TOL_OUT[dtype]
+        assert max_rel(y_multi[b], refs[b]) <= TOL_OUT[dtype]
+    assert np.array_equal(y_idx, y_multi)   # same rows, same order of operations
+
+
+# ------------------------------------------------------------------ top-k
+@pytest.mark.parametrize("n,k", [(1, 1), (7, 3), (64, 64), (688, 344), (1000, 1), (5000, 4999), (24576, 12288)])
+def test_topk_matches_oracle(n, k):
+    rng = np.random.default_rng(n * 31 + k)
+    rows = 3
+    s = rng.random((rows, n)).astype(np.float32)
+    s[1] = np.round(s[1] * 8) / 8          # many exact ties, also across the boundary
+    s[2, : n // 2] = 0.0                   # zeros (an empty-prompt statistic is all zero)
+    out = torch.full((rows, k), -1, dtype=torch.int32, device="cuda")
+    G.griffin_topk(torch.from_numpy(s).cuda(), k, out)
+    sync()
+    got = out.cpu().numpy()
+    for r in range(rows):
+        np.testing.assert_array_equal(got[r], oracle.topk(s[r], k))
+
+
+def test_stat_shared_matches_oracle():
+    rng = np.random.default_rng(8)
+    n, B = 1000, 4
+    s = rng.random((B, n)).astype(np.float32)
+    cu = [0, 10, 10, 74, 300]                # one empty sequence: skipped
+    out = torch.empty(n, dtype=torch.float32, device="cuda")
+    G.griffin_stat_shared(torch.from_numpy(s).cuda(), cu, out)
+    sync()
+    keep = [0, 2, 3]
+    ref = oracle.stat_shared(s[keep], np.array([10, 64, 226]))
+    np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=1e-6)
+
+
+# ------------------------------------------------------------------ prefill: Z, s, indices
+PREFILL_CASES = [
+    # dtype, d, F, lens, k, act, gated, bias
+    (synth.DT_F32, 256, 688, [64], 344, synth.ACT_SILU, True, False),            # config 0 shape
+    (synth.DT_F32, 72, 150, [70, 1, 33], 40, synth.ACT_GELU_TANH, True, True),   # ragged tiles, 3 seqs
+    (synth.DT_F32, 64, 130, [9], 130, synth.ACT_RELU, False, True),              # Eq. 2, keep all
+    (synth.DT_BF16, 512, 1000, [300], 500, synth.ACT_SILU, True, False),         # 3 x 8 tiles, ragged both
+    (synth.DT_BF16, 136, 260, [129, 0, 200], 77, synth.ACT_GELU_TANH, True, True),  # k tail, empty seq
+    (synth.DT_BF16, 256, 384, [256], 100, synth.ACT_RELU, False, False),         # Eq. 2 on the MFMA path
+]
+
+
+@pytest.mark.parametrize("dtype,d,F,lens,k,act,gated,bias", PREFILL_CASES)
+def test_prefill_select_matches_oracle(dtype, d, F, lens, k, act, gated, bias):
+    seed = d * 13 + F
+    c = synth.small_case(seed, d, F, max(sum(lens), 1), dtype, with_bias=bias)
+    Wg = c["Wg"] if gated else None
+    bg = c.get("bg") if gated else None
+    b1 = c.get("b1")
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    Xs = [c["X"][cu[b]:cu[b + 1]] for b in range(len(lens))]
+    live = [b for b in range(len(lens)) if lens[b] > 0]
+    W1 = c["W1"].copy()
+    nudges, s_ref_live = open_margin([Xs[b] for b in live], Wg, W1, act, dtype, [k], bg, b1)
+    L, _ = dev_layer(Wg, W1, c["W2"], act, dtype, bg, b1, c.get("b2"))
+    idx, s, Z = run_prefill(L, to_dev(c["X"], dtype), cu, k)
+    for pos, b in enumerate(live):
+        s_ref = s_ref_live[pos]
+        Z_ref = oracle.ff1(Xs[b], Wg, W1, act, bg, b1)
+        gap, _ = boundary_report(s_ref, k)
+        assert gap > 1e-3
+        assert max_rel(Z[cu[b]:cu[b + 1]], Z_ref) <= TOL_Z
+        assert max_rel(s[b], s_ref) <= TOL_S
+        assert np.sum(s[b] ** 2) == pytest.approx(lens[b], rel=1e-4)     # unit rows: sum s^2 = S
+        np.testing.assert_array_equal(idx[b], oracle.topk(s_ref, k))
+    for b in range(len(lens)):
+        if lens[b] == 0:
+            assert np.all(s[b] == 0.0)
+            np.testing.assert_array_equal(idx[b], np.arange(k))
+
+
+def test_prefill_without_z_out_and_zero_row():
+    dtype, d, F, S, k = synth.DT_F32, 64, 96, 20, 30
+    c = synth.small_case(77, d, F, S, dtype)
+    X = c["X"].copy()
+    X[5] = 0.0                               # FF_1(0) = 0 without biases: an all-zero row of Z
+    W1 = c["W1"].copy()
+    _, (s_ref,) = open_margin([X], c["Wg"], W1, synth.ACT_SILU, dtype, [k])
+    L, _ = dev_layer(c["Wg"], W1, c["W2"], synth.ACT_SILU, dtype)
+    idx, s, Z = run_prefill(L, to_dev(X, dtype), [0, S], k, want_z=False)
+    assert Z is None and np.all(np.isfinite(s))
+    assert np.sum(s[0] ** 2) == pytest.approx(S - 1, rel=1e-4)
+    assert max_rel(s[0], s_ref) <= TOL_S
+    np.testing.assert_array_equal(idx[0], oracle.topk(s_ref, k))
+
+
+# ------------------------------------------------------------------ config 0 end to end
+def test_config0_end_to_end():
+    cfg = synth.CONFIGS[0]
+    Wg, W1, W2 = synth.layer_weights(cfg, 0)
+    X = synth.prompt(cfg, 0)
+    nudges, (s_ref,) = open_margin([X], Wg, W1, cfg.act, cfg.dtype, [cfg.k])
+    idx_ref = oracle.topk(s_ref, cfg.k)
+    L, t = dev_layer(Wg, W1, W2, cfg.act, cfg.dtype)
+    idx, s, _ = run_prefill(L, to_dev(X, cfg.dtype), [0, cfg.prompt_len], cfg.k)
+    np.testing.assert_array_equal(idx[0], idx_ref)
+    assert max_rel(s[0], s_ref) <= TOL_S
+    C, ct = empty_compact(L, cfg.k, t)
+    G.griffin_compact(L, torch.from_numpy(idx[0]).cuda(), cfg.k, C)
+    cw = [oracle.compact(w, idx_ref) for w in (Wg, W1, W2)]
+    xt = synth.decode_inputs(cfg, 0)
+    for step in range(cfg.decode_steps):
+        ref = oracle.ff_decode(xt[step], *cw, cfg.act)
+        got = run_decode(C, to_dev(xt[step], cfg.dtype))
+        assert max_rel(got, ref) <= TOL_OUT[cfg.dtype]
+        full = oracle.ff_decode(xt[step], Wg, W1, W2, cfg.act)
+        assert max_rel(run_decode(L, to_dev(xt[step], cfg.dtype)), full) <= TOL_OUT[cfg.dtype]
