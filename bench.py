@@ -1,0 +1,254 @@
+#!/usr/bin/env python3
+"""Benchmark of the GRIFFIN feed-forward hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input: prompt-phase
+selection (FF activations, row normalisation, statistic s, top-k), compaction of the
+selected neurons, and T generated tokens through the pruned FF block, for every layer of the
+workload.  Inputs are resident in HBM before the timed region.  Decode cycles through enough
+copies of the compact weights (>= 1 GiB) that the 256 MB Infinity Cache cannot serve them.
+
+Prints ONE JSON line: whole-job decode tokens/s (`value`), the roofline of the dominant
+kernel (the weight-streaming decode kernel, HBM-bound) and the CPU oracle timed on a bounded
+sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=1, help="workload: index into BASELINE.json configs (1, 2 or 3)")
+    ap.add_argument("--k", type=int, default=0, help="kept neurons (default: the config's 50%% point)")
+    ap.add_argument("--layers", type=int, default=0, help="layers to run (default: all of the config)")
+    ap.add_argument("--probe-every", type=int, default=8, help="decode steps between kernel-duration probes")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--warm", action="store_true", help="single copy of the compact weights (cache-warm)")
+    return ap.parse_args()
+
+
+class Hip:
+    """The few HIP runtime calls the benchmark needs for per-kernel event timing."""
+
+    def __init__(self, torch):
+        path = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+        self.lib = ctypes.CDLL(path)
+        self.lib.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.lib.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.lib.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def event(self) -> int:
+        e = ctypes.c_void_p()
+        rc = self.lib.hipEventCreate(ctypes.byref(e))
+        if rc != 0:
+            raise RuntimeError("hipEventCreate failed: %d" % rc)
+        return e.value
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        ms = ctypes.c_float()
+        rc = self.lib.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError("hipEventElapsedTime failed: %d" % rc)
+        return float(ms.value)
+
+
+def cpu_baseline(cfg, k, Wg, W1, W2, seconds_target=12.0):
+    """The oracle as it stands, timed on this host: decode tokens through a compact block."""
+    import numpy as np
+    import oracle
+    import synth
+    S_sel = 32
+    X = synth.prompt(cfg, 0)[:S_sel]
+    idx, _ = oracle.prefill_select(X, Wg, W1, cfg.act, k)
+    cw = [oracle.compact(w, idx) for w in (Wg, W1, W2)]
+    xt = synth.decode_inputs(cfg, 0, steps=8).astype(np.float64)
+    oracle.ff_decode(xt[0], *cw, cfg.act)
+    n, t0 = 0, time.perf_counter()
+    while True:
+        oracle.ff_decode(xt[n % 8], *cw, cfg.act)
+        n += 1
+        el = time.perf_counter() - t0
+        if el >= seconds_target or n >= 512:
+            break
+    return {
+        "value": n / el, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": "%d decode tokens through one layer's k=%d compact block in fp64 (selection for the "
+                  "sample taken by the oracle on the first %d prompt rows, untimed)" % (n, k, S_sel),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU; --gpus %d is not supported (the path shards by "
+              "layer or by sequence with no communication, see DESIGN.md)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2404_01365_amd as G
+    import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    hip = Hip(torch)
+
+    cfg = synth.CONFIGS[args.config]
+    if cfg.n_seqs != 1:
+        print("bench.py: config %d is a batched parity case, not a bench line" % args.config, file=sys.stderr)
+        sys.exit(2)
+    k = args.k or cfg.k
+    n_layers = args.layers or cfg.n_layers
+    T, d, F, S = cfg.decode_steps, cfg.d, cfg.d_ff, cfg.prompt_len
+    w = 2 if cfg.dtype == synth.DT_BF16 else 4
+    tdt = torch.bfloat16 if cfg.dtype == synth.DT_BF16 else torch.float32
+
+    def up(a):
+        if cfg.dtype == synth.DT_BF16:
+            return torch.from_numpy(synth.bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+    # ---------------- inputs resident in HBM
+    layers, host_w0 = [], None
+    for l in range(n_layers):
+        Wg, W1, W2 = synth.layer_weights(cfg, l)
+        if l == 0:
+            host_w0 = (Wg, W1, W2)
+        t = dict(Wg=up(Wg), W1=up(W1), W2=up(W2), X=up(synth.prompt(cfg, l)), xt=up(synth.decode_inputs(cfg, l)))
+        t["L"] = G.layer(t["W1"], t["W2"], t["Wg"], act=cfg.act)
+        layers.append(t)
+        del Wg, W1, W2
+
+    compact_bytes = 3 * k * d * w
+    if args.warm or n_layers * compact_bytes >= (1 << 30):
+        n_rep = 1
+    else:
+        n_rep = -(-(1 << 30) // (n_layers * compact_bytes))
+    for t in layers:
+        t["C"], t["Ct"] = [], []
+        for r in range(n_rep):
+            ct = dict(Wg=torch.empty((k, d), dtype=tdt, device="cuda"), W1=torch.empty((k, d), dtype=tdt, device="cuda"),
+                      W2=torch.empty((k, d), dtype=tdt, device="cuda"))
+            t["Ct"].append(ct)
+            t["C"].append(G.layer(ct["W1"], ct["W2"], ct["Wg"], act=cfg.act))
+        t["idx"] = torch.empty((1, k), dtype=torch.int32, device="cuda")
+        t["y"] = torch.empty((T, d), dtype=tdt, device="cuda")
+    ws_pre = torch.empty(G.griffin_prefill_workspace_bytes(layers[0]["L"], S, 1, False), dtype=torch.uint8, device="cuda")
+    ws_dec = torch.empty(G.griffin_decode_workspace_bytes(d, k, 1), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    cu = [0, S]
+
+    def select_and_compact(t, rep):
+        G.griffin_prefill_select(t["L"], t["X"], cu, k, t["idx"], workspace=ws_pre, stream=stream)
+        G.griffin_compact(t["L"], t["idx"], k, t["C"][rep], stream=stream)
+
+    # copies 1.. of the compact weights are made once, outside the timed region (same contents)
+    for t in layers:
+        for r in range(1, n_rep):
+            select_and_compact(t, r)
+    torch.cuda.synchronize()
+
+    # (begin, end) hipEvent pairs around the streaming decode kernel, created before timing
+    per_step = (T * n_layers + args.probe_every - 1) // args.probe_every
+    pool = [(hip.event(), hip.event()) for _ in range(per_step * args.steps)]
+    probes = []
+    stage_ev = []     # (e0, e1, e2) torch events: select+compact | decode
+    esz = d * w
+    for t in layers:
+        t["xp"], t["yp"] = t["xt"].data_ptr(), t["y"].data_ptr()
+
+    def step(record):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)] if record else None
+        if record:
+            ev[0].record()
+        for t in layers:
+            select_and_compact(t, 0)
+        if record:
+            ev[1].record()
+        for tok in range(T):
+            for li, t in enumerate(layers):
+                if record and (tok * n_layers + li) % args.probe_every == 0:
+                    pe = pool[len(probes)]
+                    probes.append(pe)
+                    G.griffin_trace_next_decode(*pe)
+                G.griffin_ff_decode(t["C"][tok % n_rep], t["xp"] + tok * esz, t["yp"] + tok * esz, 1,
+                                    workspace=ws_dec, stream=stream)
+        if record:
+            ev[2].record()
+            stage_ev.append(ev)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_per_step = wall * 1e3 / args.steps
+    sel_ms = sum(e[0].elapsed_time(e[1]) for e in stage_ev) / len(stage_ev)
+    dec_ms = sum(e[1].elapsed_time(e[2]) for e in stage_ev) / len(stage_ev)
+    kern_us = [hip.elapsed_ms(a, b) * 1e3 for a, b in probes]
+    kern_us.sort()
+    avg_us = sum(kern_us) / len(kern_us)
+    alg_bytes = 3 * k * d * w + 2 * d * w           # compact weights once + x in + y out
+    achieved = alg_bytes / (avg_us * 1e-6) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as fh:
+            traffic = json.load(fh).get("config%d_k%d" % (cfg.cid, k))
+
+    out = {
+        "metric": "pruned-FF decode tokens/s + achieved HBM GB/s; select us/layer (prefill)",
+        "value": args.steps * T / wall,
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == synth.DT_BF16 else "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "config %d: %s, d=%d D_ff=%d, prompt %d tokens, keep k=%d, batch 1, %d decode steps, %d layer(s)"
+                        % (cfg.cid, cfg.name, d, F, S, k, T, n_layers),
+            "compact_weight_copies_cycled": n_rep,
+            "cache": "warm (one copy)" if n_rep == 1 and n_layers * compact_bytes < (1 << 30) else "cold (>= 1 GiB cycled)",
+        },
+        "roofline": {
+            "bound": "hbm", "kernel": "ff_decode_kernel",
+            "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": traffic,
+            "algorithmic_bytes_per_launch": alg_bytes,
+            "avg_kernel_us": avg_us, "median_kernel_us": kern_us[len(kern_us) // 2], "launches_timed": len(kern_us),
+        },
+        "decode": {
+            "tokens_per_s_decode_only": T / (dec_ms * 1e-3),
+            "us_per_layer_token": dec_ms * 1e3 / (T * n_layers),
+            "GBps_per_layer_token": alg_bytes / (dec_ms * 1e-3 / (T * n_layers)) / 1e9,
+        },
+        "select_us_per_layer": sel_ms * 1e3 / n_layers,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, k, *host_w0)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -152,6 +152,14 @@ int griffin_ff_decode_indexed(const griffin_layer *L, const int32_t *idx, int32_
                               int32_t batch, const void *x, void *y, void *workspace,
                               size_t workspace_bytes, void *stream);
 
+/*
+ * Instrumentation for measurement (the generation phase is where the time goes, Section 5.2):
+ * the next griffin_ff_decode* call made by this thread records event_begin just before and
+ * event_end just after its weight-streaming kernel, on that call's stream, then forgets
+ * them.  Both are hipEvent_t created by the caller with timing enabled; NULL disarms.
+ */
+int griffin_trace_next_decode(void *event_begin, void *event_end);
+
 #ifdef __cplusplus
 }
 #endif

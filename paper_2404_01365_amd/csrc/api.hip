@@ -218,6 +218,12 @@ int griffin_compact(const griffin_layer *L, const int32_t *idx, int32_t k, const
     return launch_compact(*L, idx, k, *C, (hipStream_t)stream);
 }
 
+int griffin_trace_next_decode(void *event_begin, void *event_end)
+{
+    set_decode_probe((hipEvent_t)event_begin, (hipEvent_t)event_end);
+    return GRIFFIN_OK;
+}
+
 size_t griffin_decode_workspace_bytes(int32_t d, int32_t n, int32_t batch)
 {
     if (d < 1 || n < 1 || batch < 1 || batch > GRIFFIN_MAX_BATCH)

@@ -328,6 +328,15 @@ int decode_nit(int32_t d, bool bf16)
     return 0;
 }
 
+// one-shot instrumentation: events recorded around the streaming kernel of the next decode
+static thread_local hipEvent_t g_probe_begin = nullptr, g_probe_end = nullptr;
+
+void set_decode_probe(hipEvent_t begin, hipEvent_t end)
+{
+    g_probe_begin = begin;
+    g_probe_end = end;
+}
+
 int launch_decode(const DecodeJob &job, hipStream_t st)
 {
     const int nit = decode_nit(job.d, job.bf16);
@@ -358,6 +367,10 @@ int launch_decode(const DecodeJob &job, hipStream_t st)
             for (int q = 0; q < 5; ++q)
                 m.p[b][q] = nullptr;
     }
+    const hipEvent_t ev_begin = g_probe_begin, ev_end = g_probe_end;
+    g_probe_begin = g_probe_end = nullptr;
+    if (ev_begin && hipEventRecord(ev_begin, st) != hipSuccess)
+        return set_hip_error(hipGetLastError(), "hipEventRecord");
     int rc = job.bf16 ? launch_nit<true>(nit, p, job.multi ? &m : nullptr, job.batch, st)
                       : launch_nit<false>(nit, p, job.multi ? &m : nullptr, job.batch, st);
     if (rc != GRIFFIN_OK)
@@ -365,6 +378,8 @@ int launch_decode(const DecodeJob &job, hipStream_t st)
     rc = check_launch("ff_decode_kernel");
     if (rc != GRIFFIN_OK)
         return rc;
+    if (ev_end && hipEventRecord(ev_end, st) != hipSuccess)
+        return set_hip_error(hipGetLastError(), "hipEventRecord");
 
     dim3 rgrid((job.d + 31) / 32, job.batch), rblock(256);
     if (job.multi) {
