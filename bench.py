@@ -49,6 +49,12 @@ class Hip:
         self.lib.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
         self.lib.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
         self.lib.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.lib.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+
+    def record(self, ev: int, stream) -> None:
+        rc = self.lib.hipEventRecord(ev, stream)
+        if rc != 0:
+            raise RuntimeError("hipEventRecord failed: %d" % rc)
 
     def event(self) -> int:
         e = ctypes.c_void_p()
@@ -142,10 +148,10 @@ def main():
     for t in layers:
         t["C"], t["Ct"] = [], []
         for r in range(n_rep):
-            ct = dict(Wg=torch.empty((k, d), dtype=tdt, device="cuda"), W1=torch.empty((k, d), dtype=tdt, device="cuda"),
-                      W2=torch.empty((k, d), dtype=tdt, device="cuda"))
-            t["Ct"].append(ct)
-            t["C"].append(G.layer(ct["W1"], ct["W2"], ct["Wg"], act=cfg.act))
+            # the three rows of a kept neuron side by side: [k][3][d], row stride 3d
+            blk = torch.empty((k, 3, d), dtype=tdt, device="cuda")
+            t["Ct"].append(blk)
+            t["C"].append(G.layer(blk[:, 1], blk[:, 2], blk[:, 0], act=cfg.act))
         t["idx"] = torch.empty((1, k), dtype=torch.int32, device="cuda")
         t["y"] = torch.empty((T, d), dtype=tdt, device="cuda")
     ws_pre = torch.empty(G.griffin_prefill_workspace_bytes(layers[0]["L"], S, 1, False), dtype=torch.uint8, device="cuda")
@@ -165,7 +171,7 @@ def main():
 
     # (begin, end) hipEvent pairs around the streaming decode kernel, created before timing
     per_step = (T * n_layers + args.probe_every - 1) // args.probe_every
-    pool = [(hip.event(), hip.event()) for _ in range(per_step * args.steps)]
+    pool = [(hip.event(), hip.event(), hip.event()) for _ in range(per_step * args.steps)]
     probes = []
     stage_ev = []     # (e0, e1, e2) torch events: select+compact | decode
     esz = d * w
@@ -204,9 +210,20 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     sel_ms = sum(e[0].elapsed_time(e[1]) for e in stage_ev) / len(stage_ev)
     dec_ms = sum(e[1].elapsed_time(e[2]) for e in stage_ev) / len(stage_ev)
-    kern_us = [hip.elapsed_ms(a, b) * 1e3 for a, b in probes]
-    kern_us.sort()
+    # Probed tokens carry three events: before the streaming kernel, between it and the small
+    # partial-sum kernel, after the latter.  Every recorded event costs GPU time of its own;
+    # that cost is measured in the same run: a probed token takes B = end - begin, an unprobed
+    # one takes u (from the whole decode span), the two extra events cost (B - u) / 2 each.
+    raw_main = [hip.elapsed_ms(a, m) * 1e3 for a, m, e in probes]
+    raw_tok = [hip.elapsed_ms(a, e) * 1e3 for a, m, e in probes]
+    n_tok = args.steps * T * n_layers
+    span_us = sum(e[1].elapsed_time(e[2]) for e in stage_ev) * 1e3
+    B = sum(raw_tok) / len(raw_tok)
+    u = (span_us - len(probes) * B) / (n_tok - len(probes))
+    event_overhead_us = max((B - u) / 2.0, 0.0)
+    kern_us = sorted(max(v - event_overhead_us, 0.0) for v in raw_main)
     avg_us = sum(kern_us) / len(kern_us)
+    raw_us = raw_main
     alg_bytes = 3 * k * d * w + 2 * d * w           # compact weights once + x in + y out
     achieved = alg_bytes / (avg_us * 1e-6) / 1e9
 
@@ -237,6 +254,8 @@ def main():
             "traffic": traffic,
             "algorithmic_bytes_per_launch": alg_bytes,
             "avg_kernel_us": avg_us, "median_kernel_us": kern_us[len(kern_us) // 2], "launches_timed": len(kern_us),
+            "raw_event_span_us": sum(raw_us) / len(raw_us), "event_cost_us": event_overhead_us,
+            "unprobed_us_per_layer_token": u,
         },
         "decode": {
             "tokens_per_s_decode_only": T / (dec_ms * 1e-3),

@@ -154,11 +154,12 @@ int griffin_ff_decode_indexed(const griffin_layer *L, const int32_t *idx, int32_
 
 /*
  * Instrumentation for measurement (the generation phase is where the time goes, Section 5.2):
- * the next griffin_ff_decode* call made by this thread records event_begin just before and
- * event_end just after its weight-streaming kernel, on that call's stream, then forgets
- * them.  Both are hipEvent_t created by the caller with timing enabled; NULL disarms.
+ * the next griffin_ff_decode* call made by this thread records, on that call's stream,
+ * event_begin just before its weight-streaming kernel, event_mid between that kernel and the
+ * small kernel that sums the partial rows, and event_end after the latter; then it forgets
+ * them.  All are hipEvent_t created by the caller with timing enabled; any may be NULL.
  */
-int griffin_trace_next_decode(void *event_begin, void *event_end);
+int griffin_trace_next_decode(void *event_begin, void *event_mid, void *event_end);
 
 #ifdef __cplusplus
 }

@@ -67,7 +67,7 @@ _SIGS = {
     "griffin_stat_shared": (ctypes.c_int, [_vp, _IP, _i32, _i32, _vp, _vp]),
     "griffin_compact": (ctypes.c_int, [_LP, _vp, _i32, _LP, _vp]),
     "griffin_decode_workspace_bytes": (_sz, [_i32, _i32, _i32]),
-    "griffin_trace_next_decode": (ctypes.c_int, [_vp, _vp]),
+    "griffin_trace_next_decode": (ctypes.c_int, [_vp, _vp, _vp]),
     "griffin_ff_decode": (ctypes.c_int, [_LP, _vp, _vp, _i32, _vp, _sz, _vp]),
     "griffin_ff_decode_multi": (ctypes.c_int, [_LP, _i32, _vp, _vp, _vp, _sz, _vp]),
     "griffin_ff_decode_indexed": (ctypes.c_int, [_LP, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
@@ -201,6 +201,7 @@ def griffin_ff_decode_indexed(L: griffin_layer, idx, k: int, batch: int, x, y, *
            "griffin_ff_decode_indexed")
 
 
-def griffin_trace_next_decode(event_begin: Optional[int], event_end: Optional[int]) -> None:
-    """Arm one-shot hipEvent_t handles around the next decode call's streaming kernel."""
-    _check(lib.griffin_trace_next_decode(event_begin, event_end), "griffin_trace_next_decode")
+def griffin_trace_next_decode(event_begin: Optional[int], event_mid: Optional[int],
+                              event_end: Optional[int]) -> None:
+    """Arm one-shot hipEvent_t handles before / between / after the next decode call's two kernels."""
+    _check(lib.griffin_trace_next_decode(event_begin, event_mid, event_end), "griffin_trace_next_decode")

@@ -218,9 +218,9 @@ int griffin_compact(const griffin_layer *L, const int32_t *idx, int32_t k, const
     return launch_compact(*L, idx, k, *C, (hipStream_t)stream);
 }
 
-int griffin_trace_next_decode(void *event_begin, void *event_end)
+int griffin_trace_next_decode(void *event_begin, void *event_mid, void *event_end)
 {
-    set_decode_probe((hipEvent_t)event_begin, (hipEvent_t)event_end);
+    set_decode_probe((hipEvent_t)event_begin, (hipEvent_t)event_mid, (hipEvent_t)event_end);
     return GRIFFIN_OK;
 }
 

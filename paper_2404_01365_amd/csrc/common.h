@@ -137,6 +137,6 @@ struct DecodeJob {
 };
 int launch_decode(const DecodeJob &job, hipStream_t st);
 int decode_parts(int32_t n, int32_t batch);
-void set_decode_probe(hipEvent_t begin, hipEvent_t end);
+void set_decode_probe(hipEvent_t begin, hipEvent_t mid, hipEvent_t end);
 
 }  // namespace griffin

@@ -2,21 +2,32 @@
 // (Section 4.2 "Generation with Expert Neurons"; Eq. 1 and Eq. 4-5):
 //     z_j = sigma(wg_j . x + bg_j) * (w1_j . x + b1_j),   y = sum_j z_j W2[j][:] + b2.
 //
-// The work is a single pass over 3*n*d weights at one flop per byte, so the kernel is built to
-// keep HBM busy: the three matrices are neuron-major, a wavefront owns a neuron, streams its
-// three contiguous rows with 16-byte loads (all issued before the first use), reduces the two
-// dot products with DPP (no LDS), and folds z_j * W2[j][:] into per-lane fp32 accumulators.
-// A workgroup covers a contiguous slab of neurons; its waves are folded through LDS once at
-// the end and the workgroup writes one fp32 partial row.  A second, tiny kernel sums the
-// partial rows in a fixed order (deterministic), adds b2 and converts to the output type.
+// One pass over 3*n*d weights at one flop per byte: the kernel is shaped by what HBM likes.
+// Measured on MI355X, read bandwidth is highest when the requests in flight at any moment
+// cover a compact window of addresses and each CU keeps only ~32-64 KB outstanding; many
+// lightly loaded waves beat few waves with deep queues.  So:
+//   * a TEAM of R wavefronts owns a neuron: wave r streams the r-th 1 KB piece of the
+//     neuron's three rows (16 bytes per lane), so a wave holds only its slab of x (one chunk)
+//     and of y (one chunk of fp32 accumulators) and registers do not limit occupancy;
+//   * teams take neurons round-robin across the whole chip (team T, step s -> neurons
+//     (s*NT + T)*G ... +G-1), so at any time the chip reads one contiguous window of rows
+//     per matrix (one window in all when the three rows of a neuron are stored side by
+//     side, i.e. Wg, W1, W2 interleaved with ld = 3d);
+//   * the two dot products are reduced inside the wave with DPP, combined across the team's
+//     waves through a few LDS words and one barrier per G neurons, and the next G neurons'
+//     loads are already in flight while that happens (register double buffer; the loads are
+//     branch-free so the compiler waits for the older buffer only);
+//   * each workgroup folds its teams' y slabs in LDS (one team for rows of 4 KB and more) and
+//     writes one fp32 partial row; a second tiny kernel adds the partial rows in a fixed
+//     order (deterministic), adds b2 and converts to the output type.
 #include "common.h"
 
 namespace griffin {
 
-constexpr int DEC_WAVES = 8;
-constexpr int DEC_THREADS = DEC_WAVES * 64;
-constexpr int DEC_LDS_FLOATS = 16384;   // 64 KB fold buffer
-constexpr int DEC_MAX_PARTS = 256;
+constexpr int DEC_G = 1;                 // neurons per team step
+constexpr int DEC_MAX_WAVES = 16;        // waves per workgroup
+constexpr int DEC_MAX_PARTS = 256;       // partial rows per batch row
+constexpr int DEC_FOLD_FLOATS = 8192;    // LDS floats for folding teams (d <= 8192)
 
 struct DecodeParams {
     const void *Wg, *W1, *W2, *bg, *b1;
@@ -25,6 +36,7 @@ struct DecodeParams {
     float *part;
     int64_t ld;
     int32_t d, n, n_src, act, P;
+    int32_t R, teams;        // waves per team, teams per workgroup
 };
 
 struct MultiPtrs {
@@ -32,19 +44,23 @@ struct MultiPtrs {
 };
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-// A 16-byte chunk of a row: 8 bf16 or 4 fp32 elements.  x stays in its storage form in
-// registers (packed bf16 pairs feed v_dot2_f32_bf16 directly; fp32 feeds FMA).
+// by value on purpose: bit-casting a vector element expression (v.y) in place picks element 0
+__device__ __forceinline__ bf16x2 as_bf16x2(uint32_t v) { return __builtin_bit_cast(bf16x2, v); }
+
+// A 16-byte chunk of a row: 8 bf16 or 4 fp32 elements.
 template <bool BF16>
 struct Chunk {
-    static constexpr int E = BF16 ? 8 : 4;   // elements per chunk
-    static __device__ __forceinline__ float dot(const uint4 &w, const uint4 &x, float acc)
+    static constexpr int E = BF16 ? 8 : 4;
+    static __device__ __forceinline__ float dot(const u32x4 &w, const u32x4 &x)
     {
+        float acc = 0.0f;
         if (BF16) {
-            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.x), __builtin_bit_cast(bf16x2, x.x), acc, false);
-            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.y), __builtin_bit_cast(bf16x2, x.y), acc, false);
-            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.z), __builtin_bit_cast(bf16x2, x.z), acc, false);
-            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.w), __builtin_bit_cast(bf16x2, x.w), acc, false);
+            acc = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(w.x), as_bf16x2(x.x), acc, false);
+            acc = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(w.y), as_bf16x2(x.y), acc, false);
+            acc = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(w.z), as_bf16x2(x.z), acc, false);
+            acc = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(w.w), as_bf16x2(x.w), acc, false);
         } else {
             acc = fmaf(__uint_as_float(w.x), __uint_as_float(x.x), acc);
             acc = fmaf(__uint_as_float(w.y), __uint_as_float(x.y), acc);
@@ -53,13 +69,13 @@ struct Chunk {
         }
         return acc;
     }
-    static __device__ __forceinline__ void axpy(float z, const uint4 &w, float (&y)[BF16 ? 8 : 4])
+    static __device__ __forceinline__ void axpy(float z, const u32x4 &w, float (&y)[8])
     {
         if (BF16) {
             y[0] = fmaf(z, bf16_lo(w.x), y[0]); y[1] = fmaf(z, bf16_hi(w.x), y[1]);
             y[2] = fmaf(z, bf16_lo(w.y), y[2]); y[3] = fmaf(z, bf16_hi(w.y), y[3]);
-            y[4 % E] = fmaf(z, bf16_lo(w.z), y[4 % E]); y[5 % E] = fmaf(z, bf16_hi(w.z), y[5 % E]);
-            y[6 % E] = fmaf(z, bf16_lo(w.w), y[6 % E]); y[7 % E] = fmaf(z, bf16_hi(w.w), y[7 % E]);
+            y[4] = fmaf(z, bf16_lo(w.z), y[4]); y[5] = fmaf(z, bf16_hi(w.z), y[5]);
+            y[6] = fmaf(z, bf16_lo(w.w), y[6]); y[7] = fmaf(z, bf16_hi(w.w), y[7]);
         } else {
             y[0] = fmaf(z, __uint_as_float(w.x), y[0]); y[1] = fmaf(z, __uint_as_float(w.y), y[1]);
             y[2] = fmaf(z, __uint_as_float(w.z), y[2]); y[3] = fmaf(z, __uint_as_float(w.w), y[3]);
@@ -67,200 +83,195 @@ struct Chunk {
     }
 };
 
-template <bool BF16, int NIT>
+// GATED and INDEXED are compile-time so that the three row loads of a neuron are issued
+// back to back with no branch between them (a branch there makes the compiler wait for the
+// first load before issuing the next).
+template <bool BF16, bool GATED, bool INDEXED, bool BIAS>
 __device__ __forceinline__ void decode_body(const DecodeParams &p, const void *Wg, const void *W1,
                                             const void *W2, const void *bg, const void *b1,
-                                            float *lds)
+                                            float (*red)[2 * DEC_G][16], float *fold)
 {
     constexpr int E = Chunk<BF16>::E;
     constexpr int ES = BF16 ? 2 : 4;
+    constexpr int G = DEC_G;
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, in an SGPR
+    const int R = p.R;
+    const int team = wave / R, wt = wave - team * R;
     const int b = blockIdx.y;
-    const int part_id = blockIdx.x;
-    const int d = p.d;
-    const int nch = d / E;
+    const int d = p.d, nch = d / E;
 
-    // x[b] into registers; lanes past the end hold zeros so clamped loads add nothing
-    uint4 xr[NIT];
-    const uint4 *xrow = (const uint4 *)((const char *)p.x + (int64_t)b * d * ES);
-#pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-        const int c = it * 64 + lane;
-        xr[it] = c < nch ? xrow[c] : make_uint4(0, 0, 0, 0);
-    }
+    const int c = wt * 64 + lane;            // this lane's 16-byte chunk of every row
+    const bool valid = c < nch;
+    const int cc = valid ? c : nch - 1;      // clamped: loads stay in bounds, x = 0 kills the terms
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    const u32x4 xr = valid ? ((const u32x4 *)((const char *)p.x + (int64_t)b * d * ES))[cc] : zero4;
 
-    float ya[NIT][E];
+    float ya[8];
 #pragma unroll
-    for (int it = 0; it < NIT; ++it)
-#pragma unroll
-        for (int e = 0; e < E; ++e)
-            ya[it][e] = 0.0f;
+    for (int e = 0; e < 8; ++e)
+        ya[e] = 0.0f;
 
-    int cc[NIT];
-#pragma unroll
-    for (int it = 0; it < NIT; ++it)
-        cc[it] = min(it * 64 + lane, nch - 1);
-
-    const int lo = (int)(((int64_t)p.n * part_id) / p.P);
-    const int hi = (int)(((int64_t)p.n * (part_id + 1)) / p.P);
-    const int32_t *idx = p.idx ? p.idx + (int64_t)b * p.n : nullptr;
+    const int NT = gridDim.x * p.teams;              // teams on the chip for this batch row
+    const int T = blockIdx.x * p.teams + team;
+    const int nsteps = (p.n + NT * G - 1) / (NT * G);
+    const int32_t *idx = INDEXED ? p.idx + (int64_t)b * p.n : nullptr;
     const int64_t row_bytes = p.ld * ES;
+    float(*myred)[2 * G][16] = red + team * 2;       // [parity][value][wave of the team]
 
-    for (int j = lo + wave; j < hi; j += DEC_WAVES) {
-        int row = j;
-        if (idx) {
-            row = idx[j];
-            row = row < 0 ? 0 : (row >= p.n_src ? p.n_src - 1 : row);
-        }
-        const uint4 *r1 = (const uint4 *)((const char *)W1 + row * row_bytes);
-        const uint4 *r2 = (const uint4 *)((const char *)W2 + row * row_bytes);
-        uint4 v1[NIT], v2[NIT];
-        float g = 0.0f, u = 0.0f;
-        if (Wg) {
-            const uint4 *rg = (const uint4 *)((const char *)Wg + row * row_bytes);
-            uint4 vg[NIT];
-#pragma unroll
-            for (int it = 0; it < NIT; ++it)
-                vg[it] = rg[cc[it]];
-#pragma unroll
-            for (int it = 0; it < NIT; ++it)
-                v1[it] = r1[cc[it]];
-#pragma unroll
-            for (int it = 0; it < NIT; ++it)
-                v2[it] = r2[cc[it]];
-#pragma unroll
-            for (int it = 0; it < NIT; ++it)
-                g = Chunk<BF16>::dot(vg[it], xr[it], g);
-        } else {
-#pragma unroll
-            for (int it = 0; it < NIT; ++it)
-                v1[it] = r1[cc[it]];
-#pragma unroll
-            for (int it = 0; it < NIT; ++it)
-                v2[it] = r2[cc[it]];
-        }
-#pragma unroll
-        for (int it = 0; it < NIT; ++it)
-            u = Chunk<BF16>::dot(v1[it], xr[it], u);
-        u = wave_sum(u);
-        if (b1)
-            u += load_scalar<BF16>(b1, row);
-        float z;
-        if (Wg) {
-            g = wave_sum(g);
-            if (bg)
-                g += load_scalar<BF16>(bg, row);
-            z = act_apply(p.act, g) * u;
-        } else {
-            z = act_apply(p.act, u);
-        }
-#pragma unroll
-        for (int it = 0; it < NIT; ++it)
-            Chunk<BF16>::axpy(z, v2[it], ya[it]);
+    // zero the padding entries of the cross-wave buffers once
+    for (int i = threadIdx.x; i < p.teams * 2 * 2 * G * 16; i += blockDim.x)
+        (&red[0][0][0])[i] = 0.0f;
+    __syncthreads();
+
+    // Loads are branch-free (slots past the last neuron re-read the last row, which stays in
+    // L2, and are masked when z is formed) so that the compiler can wait for exactly the
+    // older buffer while the newer one is still in flight.
+    u32x4 buf[2][G][3];
+    int rows[2][G];
+    float bias[2][G][2];
+
+#define DEC_LOAD(B_, s_)                                                                     \
+    {                                                                                        \
+        _Pragma("unroll") for (int g = 0; g < G; ++g)                                        \
+        {                                                                                    \
+            const int j_ = min(((s_) * NT + T) * G + g, p.n - 1);                            \
+            int row_ = j_;                                                                   \
+            if (INDEXED) {                                                                   \
+                row_ = idx[j_];                                                              \
+                row_ = row_ < 0 ? 0 : (row_ >= p.n_src ? p.n_src - 1 : row_);                \
+            }                                                                                \
+            if (GATED)                                                                       \
+                buf[B_][g][0] = ((const u32x4 *)((const char *)Wg + row_ * row_bytes))[cc];  \
+            buf[B_][g][1] = ((const u32x4 *)((const char *)W1 + row_ * row_bytes))[cc];      \
+            buf[B_][g][2] = ((const u32x4 *)((const char *)W2 + row_ * row_bytes))[cc];      \
+            if (BIAS) {                                                                      \
+                bias[B_][g][0] = (GATED && bg) ? load_scalar<BF16>(bg, row_) : 0.0f;         \
+                bias[B_][g][1] = b1 ? load_scalar<BF16>(b1, row_) : 0.0f;                    \
+            }                                                                                \
+            rows[B_][g] = row_;                                                              \
+        }                                                                                    \
     }
 
-    // fold the workgroup's waves through LDS: each round the upper `h` active waves park their
-    // accumulators in h slots and the lower h waves add them (fixed order, deterministic)
-    const int slots = min(DEC_WAVES / 2, DEC_LDS_FLOATS / d);
-    int active = DEC_WAVES;
-    while (active > 1) {
-        const int h = min(slots, active / 2);
-        if (wave >= active - h && wave < active) {
-            float *slot = lds + (int64_t)(wave - (active - h)) * d;
+#define DEC_CONSUME(B_, s_)                                                                  \
+    {                                                                                        \
+        float pv_[2 * G];                                                                    \
+        _Pragma("unroll") for (int g = 0; g < G; ++g)                                        \
+        {                                                                                    \
+            pv_[2 * g] = GATED ? wave_sum(Chunk<BF16>::dot(buf[B_][g][0], xr)) : 0.0f;       \
+            pv_[2 * g + 1] = wave_sum(Chunk<BF16>::dot(buf[B_][g][1], xr));                  \
+        }                                                                                    \
+        if (lane == 0) {                                                                     \
+            _Pragma("unroll") for (int v = 0; v < 2 * G; ++v) myred[(s_) & 1][v][wt] = pv_[v]; \
+        }                                                                                    \
+        __syncthreads();                                                                     \
+        float q_ = lane < 2 * G * 16 ? myred[(s_) & 1][lane >> 4][lane & 15] : 0.0f;         \
+        q_ = row16_sum(q_);                                                                  \
+        _Pragma("unroll") for (int g = 0; g < G; ++g)                                        \
+        {                                                                                    \
+            const int j_ = ((s_) * NT + T) * G + g;                                          \
+            float gg_ = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(q_), 32 * g));      \
+            float uu_ = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(q_), 32 * g + 16)); \
+            if (BIAS) {                                                                      \
+                gg_ += bias[B_][g][0];                                                       \
+                uu_ += bias[B_][g][1];                                                       \
+            }                                                                                \
+            float z_ = GATED ? act_apply(p.act, gg_) * uu_ : act_apply(p.act, uu_);          \
+            z_ = j_ < p.n ? z_ : 0.0f;                                                       \
+            Chunk<BF16>::axpy(z_, buf[B_][g][2], ya);                                        \
+        }                                                                                    \
+    }
+
+    if (nsteps > 0) {
+        DEC_LOAD(0, 0)
+        int s = 0;
+        while (s + 2 < nsteps) {
+            DEC_LOAD(1, s + 1)
+            DEC_CONSUME(0, s)
+            DEC_LOAD(0, s + 2)
+            DEC_CONSUME(1, s + 1)
+            s += 2;
+        }
+        if (s + 1 < nsteps) {
+            DEC_LOAD(1, s + 1)
+            DEC_CONSUME(0, s)
+            DEC_CONSUME(1, s + 1)
+        } else {
+            DEC_CONSUME(0, s)
+        }
+    }
+#undef DEC_LOAD
+#undef DEC_CONSUME
+    (void)rows;
+
+    // fold the workgroup's teams (fixed order), then one fp32 partial row per workgroup
+    for (int t = 1; t < p.teams; ++t) {
+        if (team == t && valid) {
 #pragma unroll
-            for (int it = 0; it < NIT; ++it) {
-                const int c = it * 64 + lane;
-                if (c < nch) {
+            for (int e = 0; e < E; e += 4)
+                *(float4 *)(fold + c * E + e) = make_float4(ya[e], ya[e + 1], ya[e + 2], ya[e + 3]);
+        }
+        __syncthreads();
+        if (team == 0 && valid) {
 #pragma unroll
-                    for (int e = 0; e < E; e += 4)
-                        *(float4 *)(slot + c * E + e) =
-                            make_float4(ya[it][e], ya[it][e + 1], ya[it][e + 2], ya[it][e + 3]);
-                }
+            for (int e = 0; e < E; e += 4) {
+                const float4 v = *(const float4 *)(fold + c * E + e);
+                ya[e] += v.x; ya[e + 1] += v.y; ya[e + 2] += v.z; ya[e + 3] += v.w;
             }
         }
         __syncthreads();
-        if (wave < h) {
-            const float *slot = lds + (int64_t)wave * d;
-#pragma unroll
-            for (int it = 0; it < NIT; ++it) {
-                const int c = it * 64 + lane;
-                if (c < nch) {
-#pragma unroll
-                    for (int e = 0; e < E; e += 4) {
-                        float4 t = *(const float4 *)(slot + c * E + e);
-                        ya[it][e] += t.x; ya[it][e + 1] += t.y;
-                        ya[it][e + 2] += t.z; ya[it][e + 3] += t.w;
-                    }
-                }
-            }
-        }
-        __syncthreads();
-        active -= h;
     }
-
-    if (wave == 0) {
-        float *out = p.part + ((int64_t)b * p.P + part_id) * d;
+    if (team == 0 && valid) {
+        float *out = p.part + ((int64_t)b * p.P + blockIdx.x) * d + c * E;
 #pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int c = it * 64 + lane;
-            if (c < nch) {
-#pragma unroll
-                for (int e = 0; e < E; e += 4)
-                    *(float4 *)(out + c * E + e) =
-                        make_float4(ya[it][e], ya[it][e + 1], ya[it][e + 2], ya[it][e + 3]);
-            }
-        }
+        for (int e = 0; e < E; e += 4)
+            *(float4 *)(out + e) = make_float4(ya[e], ya[e + 1], ya[e + 2], ya[e + 3]);
     }
 }
 
-template <bool BF16, int NIT>
-__global__ __launch_bounds__(DEC_THREADS) void ff_decode_kernel(DecodeParams p)
+template <bool BF16, bool GATED, bool INDEXED, bool BIAS>
+__global__ __launch_bounds__(DEC_MAX_WAVES * 64) void ff_decode_kernel(DecodeParams p)
 {
-    __shared__ __attribute__((aligned(16))) float lds[DEC_LDS_FLOATS];
-    decode_body<BF16, NIT>(p, p.Wg, p.W1, p.W2, p.bg, p.b1, lds);
+    __shared__ float red[DEC_MAX_WAVES * 2][2 * DEC_G][16];
+    __shared__ __attribute__((aligned(16))) float fold[DEC_FOLD_FLOATS];
+    decode_body<BF16, GATED, INDEXED, BIAS>(p, p.Wg, p.W1, p.W2, p.bg, p.b1, red, fold);
 }
 
-template <bool BF16, int NIT>
-__global__ __launch_bounds__(DEC_THREADS) void ff_decode_multi_kernel(DecodeParams p, MultiPtrs m)
+template <bool BF16, bool GATED, bool BIAS>
+__global__ __launch_bounds__(DEC_MAX_WAVES * 64) void ff_decode_multi_kernel(DecodeParams p, MultiPtrs m)
 {
-    __shared__ __attribute__((aligned(16))) float lds[DEC_LDS_FLOATS];
+    __shared__ float red[DEC_MAX_WAVES * 2][2 * DEC_G][16];
+    __shared__ __attribute__((aligned(16))) float fold[DEC_FOLD_FLOATS];
     const void *const *q = m.p[blockIdx.y];
-    decode_body<BF16, NIT>(p, q[0], q[1], q[2], q[3], q[4], lds);
+    decode_body<BF16, GATED, false, BIAS>(p, q[0], q[1], q[2], q[3], q[4], red, fold);
 }
 
-// y[b][c] = sum_p part[b][p][c] + b2[c], p ascending; one workgroup per 32 columns of one row.
 struct B2Ptrs {
     const void *p[GRIFFIN_MAX_BATCH];    // b2 of every row's own block (multi path)
 };
 
+// y[b][c..c+3] = sum_p part[b][p][c..c+3] + b2, p taken in a fixed order.  One wavefront per
+// column quad: lane l adds rows l, l+64, ... and the wave finishes with DPP sums.
 template <bool BF16, bool MULTI>
 __global__ __launch_bounds__(256) void ff_decode_reduce_kernel(const float *part, int P, int d,
                                                                const void *b2_one, B2Ptrs b2_multi,
                                                                void *y)
 {
-    __shared__ float4 sm[32][8];
-    const int q = threadIdx.x & 7;       // column quad inside the 32-column slab
-    const int pg = threadIdx.x >> 3;     // partial-row group
+    const int lane = threadIdx.x & 63;
     const int b = blockIdx.y;
+    const int c = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 4;
+    if (c >= d)
+        return;
     const void *b2 = MULTI ? b2_multi.p[b] : b2_one;
-    const int c = blockIdx.x * 32 + q * 4;
+    const float *base = part + (int64_t)b * P * d + c;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (c < d) {
-        const float *base = part + (int64_t)b * P * d + c;
-        for (int pp = pg; pp < P; pp += 32) {
-            float4 t = *(const float4 *)(base + (int64_t)pp * d);
-            acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
-        }
+    for (int pp = lane; pp < P; pp += 64) {
+        const float4 t = *(const float4 *)(base + (int64_t)pp * d);
+        acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
     }
-    sm[pg][q] = acc;
-    __syncthreads();
-    if (threadIdx.x < 8 && c < d) {
-        float4 s = sm[0][q];
-        for (int g = 1; g < 32; ++g) {
-            float4 t = sm[g][q];
-            s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
-        }
+    float4 s;
+    s.x = wave_sum(acc.x); s.y = wave_sum(acc.y); s.z = wave_sum(acc.z); s.w = wave_sum(acc.w);
+    if (lane == 0) {
         if (b2) {
             s.x += load_scalar<BF16>(b2, c);
             s.y += load_scalar<BF16>(b2, c + 1);
@@ -279,68 +290,40 @@ __global__ __launch_bounds__(256) void ff_decode_reduce_kernel(const float *part
     }
 }
 
+// waves per team for a row of d elements, 0 if this build cannot cover it
+static int decode_team_waves(int32_t d, bool bf16)
+{
+    const int nch = d / (bf16 ? 8 : 4);
+    const int R = (nch + 63) / 64;
+    return (R <= DEC_MAX_WAVES && d <= DEC_FOLD_FLOATS) ? R : 0;
+}
+
+// workgroups (= partial rows) per batch row
 int decode_parts(int32_t n, int32_t batch)
 {
     int P = (512 + batch - 1) / batch;
     if (P > DEC_MAX_PARTS) P = DEC_MAX_PARTS;
+
     if (P < 8) P = 8;
-    const int by_work = (n + DEC_WAVES - 1) / DEC_WAVES;
+    const int by_work = (n + 2 * DEC_G - 1) / (2 * DEC_G);
     if (P > by_work) P = by_work;
     return P < 1 ? 1 : P;
 }
 
-template <bool BF16, int NIT>
-static void launch_one(const DecodeParams &p, const MultiPtrs *m, int batch, hipStream_t st)
-{
-    dim3 grid(p.P, batch), block(DEC_THREADS);
-    if (m)
-        hipLaunchKernelGGL((ff_decode_multi_kernel<BF16, NIT>), grid, block, 0, st, p, *m);
-    else
-        hipLaunchKernelGGL((ff_decode_kernel<BF16, NIT>), grid, block, 0, st, p);
-}
-
-template <bool BF16>
-static int launch_nit(int nit, const DecodeParams &p, const MultiPtrs *m, int batch, hipStream_t st)
-{
-    switch (nit) {
-    case 1: launch_one<BF16, 1>(p, m, batch, st); break;
-    case 2: launch_one<BF16, 2>(p, m, batch, st); break;
-    case 4: launch_one<BF16, 4>(p, m, batch, st); break;
-    case 6: launch_one<BF16, 6>(p, m, batch, st); break;
-    case 8: launch_one<BF16, 8>(p, m, batch, st); break;
-    case 10: launch_one<BF16, 10>(p, m, batch, st); break;
-    case 12: launch_one<BF16, 12>(p, m, batch, st); break;
-    case 16: launch_one<BF16, 16>(p, m, batch, st); break;
-    default: return GRIFFIN_EUNSUPPORTED;
-    }
-    return GRIFFIN_OK;
-}
-
-// smallest supported per-lane chunk count that covers d; 0 if d is too wide for this build
-int decode_nit(int32_t d, bool bf16)
-{
-    const int nch = d / (bf16 ? 8 : 4);
-    const int need = (nch + 63) / 64;
-    static const int sizes[] = {1, 2, 4, 6, 8, 10, 12, 16};
-    for (int s : sizes)
-        if (s >= need)
-            return s;
-    return 0;
-}
-
 // one-shot instrumentation: events recorded around the streaming kernel of the next decode
-static thread_local hipEvent_t g_probe_begin = nullptr, g_probe_end = nullptr;
+static thread_local hipEvent_t g_probe_begin = nullptr, g_probe_mid = nullptr, g_probe_end = nullptr;
 
-void set_decode_probe(hipEvent_t begin, hipEvent_t end)
+void set_decode_probe(hipEvent_t begin, hipEvent_t mid, hipEvent_t end)
 {
     g_probe_begin = begin;
+    g_probe_mid = mid;
     g_probe_end = end;
 }
 
 int launch_decode(const DecodeJob &job, hipStream_t st)
 {
-    const int nit = decode_nit(job.d, job.bf16);
-    if (nit == 0)
+    const int R = decode_team_waves(job.d, job.bf16);
+    if (R == 0)
         return GRIFFIN_EUNSUPPORTED;
     const int P = decode_parts(job.n, job.batch);
     if (job.part_bytes < (size_t)P * job.batch * job.d * sizeof(float))
@@ -351,6 +334,10 @@ int launch_decode(const DecodeJob &job, hipStream_t st)
     p.idx = job.idx; p.n_src = job.idx ? job.n_src : job.n;
     p.x = job.x; p.part = job.part; p.ld = job.ld;
     p.d = job.d; p.n = job.n; p.act = job.act; p.P = P;
+    p.R = R;
+    // about eight waves per workgroup, one workgroup per CU: measured best (more waves or
+    // more loads in flight per CU lower the achieved bandwidth)
+    p.teams = R >= 8 ? 1 : 8 / R;
 
     MultiPtrs m;
     B2Ptrs b2m;
@@ -367,21 +354,41 @@ int launch_decode(const DecodeJob &job, hipStream_t st)
             for (int q = 0; q < 5; ++q)
                 m.p[b][q] = nullptr;
     }
-    const hipEvent_t ev_begin = g_probe_begin, ev_end = g_probe_end;
-    g_probe_begin = g_probe_end = nullptr;
+
+    const hipEvent_t ev_begin = g_probe_begin, ev_mid = g_probe_mid, ev_end = g_probe_end;
+    g_probe_begin = g_probe_mid = g_probe_end = nullptr;
     if (ev_begin && hipEventRecord(ev_begin, st) != hipSuccess)
         return set_hip_error(hipGetLastError(), "hipEventRecord");
-    int rc = job.bf16 ? launch_nit<true>(nit, p, job.multi ? &m : nullptr, job.batch, st)
-                      : launch_nit<false>(nit, p, job.multi ? &m : nullptr, job.batch, st);
+
+    dim3 grid(P, job.batch), block(p.teams * R * 64);
+    const bool gated = job.multi ? job.multi[0].Wg != nullptr : job.Wg != nullptr;
+    const bool indexed = job.idx != nullptr;
+    const bool bias = job.multi ? (job.multi[0].bg || job.multi[0].b1) : (job.bg || job.b1);
+#define DEC_GO(BF, GA, IX, BI) hipLaunchKernelGGL((ff_decode_kernel<BF, GA, IX, BI>), grid, block, 0, st, p)
+#define DEC_GO_MULTI(BF, GA, BI) hipLaunchKernelGGL((ff_decode_multi_kernel<BF, GA, BI>), grid, block, 0, st, p, m)
+#define DEC_PICK3(BF, GA, IX) { if (bias) DEC_GO(BF, GA, IX, true); else DEC_GO(BF, GA, IX, false); }
+#define DEC_PICK2(BF, GA) { if (indexed) DEC_PICK3(BF, GA, true) else DEC_PICK3(BF, GA, false) }
+#define DEC_PICKM(BF, GA) { if (bias) DEC_GO_MULTI(BF, GA, true); else DEC_GO_MULTI(BF, GA, false); }
+    if (job.multi) {
+        if (job.bf16) { if (gated) DEC_PICKM(true, true) else DEC_PICKM(true, false) }
+        else          { if (gated) DEC_PICKM(false, true) else DEC_PICKM(false, false) }
+    } else if (job.bf16) {
+        if (gated) DEC_PICK2(true, true) else DEC_PICK2(true, false)
+    } else {
+        if (gated) DEC_PICK2(false, true) else DEC_PICK2(false, false)
+    }
+#undef DEC_PICK3
+#undef DEC_PICK2
+#undef DEC_PICKM
+#undef DEC_GO
+#undef DEC_GO_MULTI
+    int rc = check_launch("ff_decode_kernel");
     if (rc != GRIFFIN_OK)
         return rc;
-    rc = check_launch("ff_decode_kernel");
-    if (rc != GRIFFIN_OK)
-        return rc;
-    if (ev_end && hipEventRecord(ev_end, st) != hipSuccess)
+    if (ev_mid && hipEventRecord(ev_mid, st) != hipSuccess)
         return set_hip_error(hipGetLastError(), "hipEventRecord");
 
-    dim3 rgrid((job.d + 31) / 32, job.batch), rblock(256);
+    dim3 rgrid((job.d / 4 + 3) / 4, job.batch), rblock(256);
     if (job.multi) {
         if (job.bf16)
             hipLaunchKernelGGL((ff_decode_reduce_kernel<true, true>), rgrid, rblock, 0, st, job.part, P, job.d, b2, b2m, job.y);
@@ -393,7 +400,10 @@ int launch_decode(const DecodeJob &job, hipStream_t st)
         else
             hipLaunchKernelGGL((ff_decode_reduce_kernel<false, false>), rgrid, rblock, 0, st, job.part, P, job.d, b2, b2m, job.y);
     }
-    return check_launch("ff_decode_reduce_kernel");
+    rc = check_launch("ff_decode_reduce_kernel");
+    if (rc == GRIFFIN_OK && ev_end && hipEventRecord(ev_end, st) != hipSuccess)
+        return set_hip_error(hipGetLastError(), "hipEventRecord");
+    return rc;
 }
 
 }  // namespace griffin

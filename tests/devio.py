@@ -20,7 +20,7 @@ def to_dev(a, dtype):
 def to_host(t):
     """device tensor -> float64 host array (exact widening)."""
     if t.dtype == torch.bfloat16:
-        bits = t.view(torch.int16).cpu().numpy().view(np.uint16)
+        bits = t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
         return synth.from_bf16_bits(bits).astype(np.float64)
     return t.cpu().numpy().astype(np.float64)
 
@@ -33,13 +33,18 @@ def dev_layer(Wg, W1, W2, act, dtype, bg=None, b1=None, b2=None):
     return L, t
 
 
-def empty_compact(L, k, tensors):
-    """Caller-allocated compact block for k neurons of L."""
+def empty_compact(L, k, tensors, interleaved=False):
+    """Caller-allocated compact block for k neurons of L.  `interleaved` stores the three rows
+    of a neuron side by side ([k][3][d], row stride 3d) instead of three separate matrices."""
     W1 = tensors["W1"]
-    mk = lambda: torch.empty((k, L.d), dtype=W1.dtype, device="cuda")
     vec = lambda src: None if src is None else torch.empty((k,), dtype=W1.dtype, device="cuda")
-    c = dict(Wg=None if tensors["Wg"] is None else mk(), W1=mk(), W2=mk(),
-             bg=vec(tensors["bg"]), b1=vec(tensors["b1"]), b2=tensors["b2"])
+    if interleaved:
+        blk = torch.empty((k, 3, L.d), dtype=W1.dtype, device="cuda")
+        mats = dict(Wg=None if tensors["Wg"] is None else blk[:, 0], W1=blk[:, 1], W2=blk[:, 2])
+    else:
+        mk = lambda: torch.empty((k, L.d), dtype=W1.dtype, device="cuda")
+        mats = dict(Wg=None if tensors["Wg"] is None else mk(), W1=mk(), W2=mk())
+    c = dict(mats, bg=vec(tensors["bg"]), b1=vec(tensors["b1"]), b2=tensors["b2"])
     C = G.layer(c["W1"], c["W2"], c["Wg"], act=L.act, dtype=L.dtype, bg=c["bg"], b1=c["b1"], b2=c["b2"])
     return C, c
 

@@ -82,13 +82,14 @@ def test_ff_decode_batch_rows_are_independent():
 
 
 # ------------------------------------------------------------------ compaction
+@pytest.mark.parametrize("interleaved", [False, True])
 @pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
-def test_compact_is_a_bit_exact_row_gather(dtype):
+def test_compact_is_a_bit_exact_row_gather(dtype, interleaved):
     d, n, k = 264, 301, 97
     c = synth.small_case(11, d, n, 4, dtype, with_bias=True)
     L, t = dev_layer(c["Wg"], c["W1"], c["W2"], synth.ACT_SILU, dtype, c["bg"], c["b1"], c["b2"])
     idx = np.sort(np.random.default_rng(3).choice(n, k, replace=False)).astype(np.int32)
-    C, ct = empty_compact(L, k, t)
+    C, ct = empty_compact(L, k, t, interleaved)
     G.griffin_compact(L, torch.from_numpy(idx).cuda(), k, C)
     sync()
     for name in ("Wg", "W1", "W2", "bg", "b1"):
@@ -239,7 +240,7 @@ def test_config0_end_to_end():
     idx, s, _ = run_prefill(L, to_dev(X, cfg.dtype), [0, cfg.prompt_len], cfg.k)
     np.testing.assert_array_equal(idx[0], idx_ref)
     assert max_rel(s[0], s_ref) <= TOL_S
-    C, ct = empty_compact(L, cfg.k, t)
+    C, ct = empty_compact(L, cfg.k, t, interleaved=True)
     G.griffin_compact(L, torch.from_numpy(idx[0]).cuda(), cfg.k, C)
     cw = [oracle.compact(w, idx_ref) for w in (Wg, W1, W2)]
     xt = synth.decode_inputs(cfg, 0)
