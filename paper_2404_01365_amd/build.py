@@ -19,7 +19,7 @@ FLAGS = [
     # packed fp32 VALU forms are kept off for every kernel in this library
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
-]
+] + os.environ.get("GRIFFIN_EXTRA_FLAGS", "").split()
 
 
 def sources():

@@ -22,7 +22,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;   // one 16-byte chunk (8 bf16)
 
-constexpr int G_BM = 128, G_BN = 128, G_BK = 64;
+constexpr int G_BN = 128, G_BK = 64;
 constexpr int G_THREADS = 256;
 constexpr int F_BM = 64, F_BN = 64, F_BK = 16;
 
@@ -34,14 +34,18 @@ struct Ff1Params {
 };
 
 // ------------------------------------------------------------------------------------ bf16 / MFMA
-template <int ACT, bool GATED>
+// MI = 32-row MFMA tiles per wave along the token axis: the workgroup tile is (64*MI) tokens x
+// 128 neurons, 4 waves as 2 (tokens) x 2 (neurons), each wave (32*MI) x 64 of both products.
+template <int ACT, bool GATED, int MI, bool KTAIL>
 __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
 {
+    constexpr int BM = 64 * MI;
+    constexpr int AQ = BM / 32;      // 16-byte chunks of X a thread stages per k-tile
     // [buffer][row][8 chunks of 16 B], chunk c of row r stored at c ^ (r & 7)
-    __shared__ u32x4 As[2][G_BM * 8];
+    __shared__ u32x4 As[2][BM * 8];
     __shared__ u32x4 B1s[2][G_BN * 8];
     __shared__ u32x4 Bgs[GATED ? 2 : 1][GATED ? G_BN * 8 : 1];
-    __shared__ float rs[2][G_BM];
+    __shared__ float rs[2][BM];
 
     // XCD-aware tile order
     const int nblk = p.mt * p.nt;
@@ -50,55 +54,86 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
     if (logical >= nblk)
         return;
     const int tile_n = logical / p.mt, tile_m = logical % p.mt;
-    const int m0 = tile_m * G_BM, n0 = tile_n * G_BN;
+    const int m0 = tile_m * BM, n0 = tile_n * G_BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
 
-    // global -> register staging: thread covers chunk `lc` of rows lr + 32 p
+    // global -> register staging: thread covers chunk `lc` of rows lr + 32 q.  Row offsets are
+    // clamped once (rows past the end re-read the last row; their results are never stored).
     const int lr = tid >> 3, lc = tid & 7;
-    const uint16_t *xa[4], *w1a[4], *wga[4];
+    const uint16_t *xb = (const uint16_t *)p.X + lc * 8;
+    const uint16_t *w1b = (const uint16_t *)p.W1 + lc * 8;
+    const uint16_t *wgb = GATED ? (const uint16_t *)p.Wg + lc * 8 : nullptr;
+    int64_t xo[AQ], wo[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int row = lr + 32 * q;
-        const int gm = min(m0 + row, p.M - 1);
-        const int gn = min(n0 + row, p.F - 1);
-        xa[q] = (const uint16_t *)p.X + (int64_t)gm * p.ldx + lc * 8;
-        w1a[q] = (const uint16_t *)p.W1 + (int64_t)gn * p.ldw + lc * 8;
-        wga[q] = GATED ? (const uint16_t *)p.Wg + (int64_t)gn * p.ldw + lc * 8 : nullptr;
-    }
-    u32x4 ra[4], r1[4], rg[4];
+    for (int q = 0; q < AQ; ++q)
+        xo[q] = (int64_t)min(m0 + lr + 32 * q, p.M - 1) * p.ldx;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        wo[q] = (int64_t)min(n0 + lr + 32 * q, p.F - 1) * p.ldw;
+    u32x4 ra[AQ], r1[4], rg[4];
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
-// global -> registers for the k-tile starting at k0 (chunks past d read as zero)
+// global -> registers for the k-tile starting at k0 (with KTAIL, chunks past d read as zero)
 #define FF1_LOAD_TILE(k0)                                                     \
     {                                                                         \
-        const bool ok_ = (k0) + lc * 8 < p.d;                                 \
+        const bool ok_ = !KTAIL || (k0) + lc * 8 < p.d;                       \
+        _Pragma("unroll") for (int q = 0; q < AQ; ++q)                        \
+            ra[q] = ok_ ? *(const u32x4 *)(xb + xo[q] + (k0)) : zero4;        \
         _Pragma("unroll") for (int q = 0; q < 4; ++q)                         \
         {                                                                     \
-            ra[q] = ok_ ? *(const u32x4 *)(xa[q] + (k0)) : zero4;             \
-            r1[q] = ok_ ? *(const u32x4 *)(w1a[q] + (k0)) : zero4;            \
+            r1[q] = ok_ ? *(const u32x4 *)(w1b + wo[q] + (k0)) : zero4;       \
             if (GATED)                                                        \
-                rg[q] = ok_ ? *(const u32x4 *)(wga[q] + (k0)) : zero4;        \
+                rg[q] = ok_ ? *(const u32x4 *)(wgb + wo[q] + (k0)) : zero4;   \
         }                                                                     \
     }
 // registers -> LDS buffer `buf`
 #define FF1_STORE_TILE(buf)                                                   \
     {                                                                         \
+        _Pragma("unroll") for (int q = 0; q < AQ; ++q)                        \
+        {                                                                     \
+            const int row_ = lr + 32 * q;                                     \
+            As[buf][row_ * 8 + (lc ^ (row_ & 7))] = ra[q];                    \
+        }                                                                     \
         _Pragma("unroll") for (int q = 0; q < 4; ++q)                         \
         {                                                                     \
             const int row_ = lr + 32 * q;                                     \
             const int slot_ = row_ * 8 + (lc ^ (row_ & 7));                   \
-            As[buf][slot_] = ra[q];                                           \
             B1s[buf][slot_] = r1[q];                                          \
             if (GATED)                                                        \
                 Bgs[buf][slot_] = rg[q];                                      \
         }                                                                     \
     }
+// LDS -> MFMA operand fragments of k-step kk of buffer `buf`
+#define FF1_READ_FRAGS(F_, buf, kk)                                           \
+    {                                                                         \
+        const int ch_ = (2 * (kk) + lh) ^ sw;                                 \
+        _Pragma("unroll") for (int mi = 0; mi < MI; ++mi)                     \
+            fa[F_][mi] = As[buf][(wm * (32 * MI) + mi * 32 + l31) * 8 + ch_]; \
+        _Pragma("unroll") for (int ni = 0; ni < 2; ++ni)                      \
+        {                                                                     \
+            f1[F_][ni] = B1s[buf][(wn * 64 + ni * 32 + l31) * 8 + ch_];       \
+            if (GATED)                                                        \
+                fg[F_][ni] = Bgs[buf][(wn * 64 + ni * 32 + l31) * 8 + ch_];   \
+        }                                                                     \
+    }
+#define FF1_MFMA(F_)                                                          \
+    {                                                                         \
+        _Pragma("unroll") for (int mi = 0; mi < MI; ++mi)                     \
+            _Pragma("unroll") for (int ni = 0; ni < 2; ++ni)                  \
+        {                                                                     \
+            accU[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(           \
+                __builtin_bit_cast(bf16x8, fa[F_][mi]), __builtin_bit_cast(bf16x8, f1[F_][ni]), accU[mi][ni], 0, 0, 0); \
+            if (GATED)                                                        \
+                accG[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(       \
+                    __builtin_bit_cast(bf16x8, fa[F_][mi]), __builtin_bit_cast(bf16x8, fg[F_][ni]), accG[mi][ni], 0, 0, 0); \
+        }                                                                     \
+    }
 
-    f32x16 accU[2][2], accG[2][2];
+    f32x16 accU[MI][2], accG[MI][2];
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
@@ -108,45 +143,54 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
             }
 
     const int KT = (p.d + G_BK - 1) / G_BK;
+    const int l31 = lane & 31, lh = lane >> 5, sw = lane & 7;
+    u32x4 fa[2][MI], f1[2][2], fg[2][2];      // operand fragments, double-buffered over k-steps
+
     FF1_LOAD_TILE(0)
     FF1_STORE_TILE(0)
     __syncthreads();
+    FF1_READ_FRAGS(0, 0, 0)
 
-    const int l31 = lane & 31, lh = lane >> 5, sw = lane & 7;
+    // Per k-tile: the next tile's global loads are issued first; each k-step's MFMAs run on
+    // fragments read during the previous k-step; the staged registers go to the other LDS
+    // buffer during the last two k-steps; one barrier, then the first fragments of the next
+    // tile.
     for (int kt = 0; kt < KT; ++kt) {
         const int buf = kt & 1;
-        if (kt + 1 < KT)
+        const bool more = kt + 1 < KT;
+#ifndef FF1_LAB_NOLOAD
+        if (more)
             FF1_LOAD_TILE((kt + 1) * G_BK)
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const int ch = (2 * kk + lh) ^ sw;
-            bf16x8 a[2], b1v[2], bgv[2];
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-                a[mi] = __builtin_bit_cast(bf16x8, As[buf][(wm * 64 + mi * 32 + l31) * 8 + ch]);
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-                b1v[ni] = __builtin_bit_cast(bf16x8, B1s[buf][(wn * 64 + ni * 32 + l31) * 8 + ch]);
-                if (GATED)
-                    bgv[ni] = __builtin_bit_cast(bf16x8, Bgs[buf][(wn * 64 + ni * 32 + l31) * 8 + ch]);
-            }
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < 2; ++ni) {
-                    accU[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b1v[ni], accU[mi][ni], 0, 0, 0);
-                    if (GATED)
-                        accG[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], bgv[ni], accG[mi][ni], 0, 0, 0);
-                }
-        }
-        if (kt + 1 < KT)
+#endif
+        FF1_READ_FRAGS(1, buf, 1)
+        FF1_MFMA(0)
+        FF1_READ_FRAGS(0, buf, 2)
+        FF1_MFMA(1)
+        FF1_READ_FRAGS(1, buf, 3)
+        FF1_MFMA(0)
+#ifndef FF1_LAB_NOSTORE
+        if (more)
             FF1_STORE_TILE(buf ^ 1)
+#endif
+        FF1_MFMA(1)
         __syncthreads();
+        if (more)
+            FF1_READ_FRAGS(0, buf ^ 1, 0)
     }
 
 #undef FF1_LOAD_TILE
 #undef FF1_STORE_TILE
+#undef FF1_READ_FRAGS
+#undef FF1_MFMA
 
+#ifdef FF1_LAB_NOEPI
+    {
+        float s_ = 0.f;
+        for (int mi = 0; mi < MI; ++mi) for (int ni = 0; ni < 2; ++ni) for (int i = 0; i < 16; ++i) s_ += accU[mi][ni][i] + accG[mi][ni][i];
+        if (s_ == 1.2345f) p.Z[0] = s_;
+        return;
+    }
+#endif
     // epilogue.  Lane holds column (neuron) l31 of each 32x32 tile and rows
     // (i>>2)*8 + lh*4 + (i&3), i = 0..15.
     float b1j[2], bgj[2];
@@ -159,10 +203,10 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
         bgj[ni] = (GATED && p.bg) ? bf16_bits_to_f32(((const uint16_t *)p.bg)[cj]) : 0.0f;
     }
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi) {
+    for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const int lrow = wm * 64 + mi * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
+            const int lrow = wm * (32 * MI) + mi * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
             const int grow = m0 + lrow;
             float sq = 0.0f;
 #pragma unroll
@@ -187,8 +231,9 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
         }
     }
     __syncthreads();
-    if (tid < G_BM && m0 + tid < p.M)
-        p.rowpart[(int64_t)(m0 + tid) * p.nt + tile_n] = rs[0][tid] + rs[1][tid];
+    for (int r = tid; r < BM; r += G_THREADS)
+        if (m0 + r < p.M)
+            p.rowpart[(int64_t)(m0 + r) * p.nt + tile_n] = rs[0][r] + rs[1][r];
 }
 
 // ------------------------------------------------------------------------------------ fp32 / FMA
@@ -279,15 +324,29 @@ int ff1_ntiles(const griffin_layer &L)
     return (L.n + bn - 1) / bn;
 }
 
-template <int ACT>
+template <int ACT, int MI>
 static void launch_mfma(const Ff1Params &p, bool gated, hipStream_t st)
 {
     const int nblk = p.mt * p.nt;
     dim3 grid(((nblk + 7) / 8) * 8), block(G_THREADS);
-    if (gated)
-        hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, true>), grid, block, 0, st, p);
-    else
-        hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, false>), grid, block, 0, st, p);
+    const bool ktail = p.d % G_BK != 0;
+    if (gated) {
+        if (ktail) hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, true, MI, true>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, true, MI, false>), grid, block, 0, st, p);
+    } else {
+        if (ktail) hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, false, MI, true>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, false, MI, false>), grid, block, 0, st, p);
+    }
+}
+
+template <int MI>
+static void launch_mfma_act(const Ff1Params &p, int act, bool gated, hipStream_t st)
+{
+    switch (act) {
+    case GRIFFIN_ACT_SILU: launch_mfma<GRIFFIN_ACT_SILU, MI>(p, gated, st); break;
+    case GRIFFIN_ACT_GELU_TANH: launch_mfma<GRIFFIN_ACT_GELU_TANH, MI>(p, gated, st); break;
+    default: launch_mfma<GRIFFIN_ACT_RELU, MI>(p, gated, st); break;
+    }
 }
 
 int launch_ff1(const griffin_layer &L, const void *X, int64_t ldx, int64_t M, float *Z, int64_t ldz,
@@ -304,11 +363,13 @@ int launch_ff1(const griffin_layer &L, const void *X, int64_t ldx, int64_t M, fl
         return GRIFFIN_OK;
     const bool gated = L.Wg != nullptr;
     if (L.dtype == GRIFFIN_BF16) {
-        p.mt = (int32_t)((M + G_BM - 1) / G_BM);
-        switch (L.act) {
-        case GRIFFIN_ACT_SILU: launch_mfma<GRIFFIN_ACT_SILU>(p, gated, st); break;
-        case GRIFFIN_ACT_GELU_TANH: launch_mfma<GRIFFIN_ACT_GELU_TANH>(p, gated, st); break;
-        default: launch_mfma<GRIFFIN_ACT_RELU>(p, gated, st); break;
+        // 256-token tiles halve the LDS traffic per flop; short prompts keep 128
+        if (M > 128) {
+            p.mt = (int32_t)((M + 255) / 256);
+            launch_mfma_act<4>(p, L.act, gated, st);
+        } else {
+            p.mt = (int32_t)((M + 127) / 128);
+            launch_mfma_act<2>(p, L.act, gated, st);
         }
         return check_launch("ff1_bf16_mfma_kernel");
     }
