@@ -207,6 +207,20 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
+    # the same block at full width (k = D_ff, Eq. 1) through the same entry point, outside the
+    # timed region: decode latency of the pruned block relative to the full one
+    ws_full = torch.empty(G.griffin_decode_workspace_bytes(d, F, 1), dtype=torch.uint8, device="cuda")
+    fe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for rep in range(2):
+        if rep == 1:
+            fe[0].record()
+        for tok in range(T):
+            for t in layers:
+                G.griffin_ff_decode(t["L"], t["xp"] + tok * esz, t["yp"] + tok * esz, 1, workspace=ws_full, stream=stream)
+    fe[1].record()
+    torch.cuda.synchronize()
+    full_us = fe[0].elapsed_time(fe[1]) * 1e3 / (T * n_layers)
+
     ms_per_step = wall * 1e3 / args.steps
     sel_ms = sum(e[0].elapsed_time(e[1]) for e in stage_ev) / len(stage_ev)
     dec_ms = sum(e[1].elapsed_time(e[2]) for e in stage_ev) / len(stage_ev)
@@ -261,6 +275,8 @@ def main():
             "tokens_per_s_decode_only": T / (dec_ms * 1e-3),
             "us_per_layer_token": dec_ms * 1e3 / (T * n_layers),
             "GBps_per_layer_token": alg_bytes / (dec_ms * 1e-3 / (T * n_layers)) / 1e9,
+            "full_width_us_per_layer_token": full_us,
+            "pruned_over_full_latency": u / full_us,
         },
         "select_us_per_layer": sel_ms * 1e3 / n_layers,
     }
