@@ -33,11 +33,278 @@ struct Ff1Params {
     int32_t M, F, d, nt, mt;
 };
 
-// ------------------------------------------------------------------------------------ bf16 / MFMA
-// MI = 32-row MFMA tiles per wave along the token axis: the workgroup tile is (64*MI) tokens x
-// 128 neurons, 4 waves as 2 (tokens) x 2 (neurons), each wave (32*MI) x 64 of both products.
-template <int ACT, bool GATED, int MI, bool KTAIL>
+// Epilogue shared by the MFMA kernels: sigma, gating, store of Z, row sums of z^2.
+// Lane holds column (neuron) l31 of each 32x32 tile and rows (i>>2)*8 + lh*4 + (i&3), i = 0..15.
+template <int ACT, bool GATED, int MI>
+__device__ __forceinline__ void ff1_mfma_epilogue(const Ff1Params &p, f32x16 (&accU)[MI][2], f32x16 (&accG)[MI][2],
+                                                  float (*rs)[64 * MI], int m0, int n0, int tile_n)
+{
+    constexpr int BM = 64 * MI;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1, l31 = lane & 31, lh = lane >> 5;
+    float b1j[2], bgj[2];
+    int col[2];
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) {
+        col[ni] = n0 + wn * 64 + ni * 32 + l31;
+        const int cj = min(col[ni], p.F - 1);
+        b1j[ni] = p.b1 ? bf16_bits_to_f32(((const uint16_t *)p.b1)[cj]) : 0.0f;
+        bgj[ni] = (GATED && p.bg) ? bf16_bits_to_f32(((const uint16_t *)p.bg)[cj]) : 0.0f;
+    }
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int lrow = wm * (32 * MI) + mi * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
+            const int grow = m0 + lrow;
+            float sq = 0.0f;
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                const float u = accU[mi][ni][i] + b1j[ni];
+                float z;
+                if (GATED)
+                    z = act_apply_t<ACT>(accG[mi][ni][i] + bgj[ni]) * u;
+                else
+                    z = act_apply_t<ACT>(u);
+                if (col[ni] < p.F) {
+                    sq = fmaf(z, z, sq);
+                    if (grow < p.M)
+                        p.Z[(int64_t)grow * p.ldz + col[ni]] = z;
+                }
+            }
+            // sum over the 32 lanes that share this row
+            sq = row16_sum(sq);
+            sq += __shfl_xor(sq, 16, 64);
+            if (l31 == 0)
+                rs[wn][lrow] = sq;
+        }
+    }
+    __syncthreads();
+    for (int r = tid; r < BM; r += G_THREADS)
+        if (m0 + r < p.M)
+            p.rowpart[(int64_t)(m0 + r) * p.nt + tile_n] = rs[0][r] + rs[1][r];
+}
+
+// ------------------------------------------------------------------------------------ bf16 / MFMA, direct-to-LDS
+// Main path (d a multiple of 32).  Operand tiles go from global memory straight into LDS
+// (global_load_lds_dwordx4: lane l of a wave instruction fills 16-byte slot l of a 1 KB region,
+// no VGPR staging, no ds_write), BK = 32, four LDS stages, so three k-tiles (~3000 MFMA
+// cycles) of loads are in flight.  A row of a stage is 64 B = 4 slots; logical chunk c of row r
+// sits in slot c ^ ((r >> 1) & 3), which keeps the ds_read_b128 operand fetches conflict-free;
+// the swizzle is applied by choosing which global chunk each lane loads.  The loop body is
+// branch-free (loads past the last k-tile re-read the last one into a dead stage) so that the
+// scheduler can interleave LDS reads and loads between MFMAs: k-step 1's fragments are read
+// under k-step 0's MFMAs, the next tile's first fragments and the tile three ahead under k-step
+// 1's.  One bare s_barrier per k-tile, preceded by the vmcnt wait that says tile kt+1 landed.
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void gbl_cvoid_t;
+
+template <int ACT, bool GATED, int MI>
 __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
+{
+    constexpr int BM = 64 * MI;
+    constexpr int NS = 4, BK = 32;
+    constexpr int A_SLOTS = BM * 4, B_SLOTS = G_BN * 4;
+    constexpr int STAGE = A_SLOTS + (GATED ? 2 : 1) * B_SLOTS;
+    constexpr int AQ = MI;                       // 16-row regions of X per wave per k-tile
+    constexpr int NLOADS = AQ + (GATED ? 4 : 2);  // LDS-DMA instructions per wave per k-tile
+    // s_waitcnt immediates: vmcnt in bits [3:0] and [15:14], expcnt/lgkmcnt fields left at "no wait"
+    constexpr int WAIT_ONE_TILE = 0x0F70 | (NLOADS & 15) | ((NLOADS >> 4) << 14);
+    constexpr int WAIT_TWO_TILES = 0x0F70 | ((2 * NLOADS) & 15) | (((2 * NLOADS) >> 4) << 14);
+    __shared__ u32x4 lds[NS * STAGE];
+    __shared__ float rs[2][BM];
+
+    // XCD-aware tile order
+    const int nblk = p.mt * p.nt;
+    const int per_xcd = (nblk + 7) / 8;
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= nblk)
+        return;
+    const int tile_n = logical / p.mt, tile_m = logical % p.mt;
+    const int m0 = tile_m * BM, n0 = tile_n * G_BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // loader: lane -> (row of the region, slot in the row) -> global chunk (un-swizzled)
+    const int lrow = lane >> 2, lp = lane & 3;
+    int64_t xoff[AQ], woff[2];
+#pragma unroll
+    for (int q = 0; q < AQ; ++q) {
+        const int row = (wave * AQ + q) * 16 + lrow;
+        xoff[q] = (int64_t)min(m0 + row, p.M - 1) * p.ldx + (lp ^ ((row >> 1) & 3)) * 8;
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int row = (wave * 2 + q) * 16 + lrow;
+        woff[q] = (int64_t)min(n0 + row, p.F - 1) * p.ldw + (lp ^ ((row >> 1) & 3)) * 8;
+    }
+    const uint16_t *Xp = (const uint16_t *)p.X, *W1p = (const uint16_t *)p.W1, *Wgp = (const uint16_t *)p.Wg;
+    const int KT = p.d / BK;
+
+#define FF1_ISSUE(kt_)                                                                                   \
+    {                                                                                                    \
+        u32x4 *st_ = lds + ((kt_) % NS) * STAGE;                                                         \
+        const int k0_ = min((kt_), KT - 1) * BK;                                                         \
+        _Pragma("unroll") for (int q = 0; q < AQ; ++q)                                                   \
+            __builtin_amdgcn_global_load_lds((gbl_cvoid_t *)(Xp + xoff[q] + k0_),                        \
+                                             (lds_void_t *)(st_ + (wave * AQ + q) * 64), 16, 0, 0);      \
+        _Pragma("unroll") for (int q = 0; q < 2; ++q)                                                    \
+            __builtin_amdgcn_global_load_lds((gbl_cvoid_t *)(W1p + woff[q] + k0_),                       \
+                                             (lds_void_t *)(st_ + A_SLOTS + (wave * 2 + q) * 64), 16, 0, 0); \
+        if (GATED) {                                                                                     \
+            _Pragma("unroll") for (int q = 0; q < 2; ++q)                                                \
+                __builtin_amdgcn_global_load_lds((gbl_cvoid_t *)(Wgp + woff[q] + k0_),                   \
+                                                 (lds_void_t *)(st_ + A_SLOTS + B_SLOTS + (wave * 2 + q) * 64), 16, 0, 0); \
+        }                                                                                                \
+    }
+// Operand fragments are fetched with ds_read_b128 written as inline asm: the compiler makes every
+// LDS load it knows about wait for ALL LDS-DMA in flight (it cannot tell the stages apart), which
+// would serialise the pipeline.  The asm reads are invisible to that logic; their completion is
+// awaited explicitly (FF1_WAIT_FRAGS names the registers, so the MFMAs that use them stay behind
+// it), and sched_barrier keeps the hand-made interleaving of reads, DMA issues and MFMAs.
+#define FF1_DS_READ(dst, addr, off) asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"((addr) + (uint32_t)(off)))
+#define FF1_BARRIER()                                                                                    \
+    {                                                                                                    \
+        asm volatile("" ::: "memory");                                                                   \
+        __builtin_amdgcn_s_barrier();                                                                    \
+        asm volatile("" ::: "memory");                                                                   \
+    }
+#define FF1_PIN() __builtin_amdgcn_sched_barrier(0)
+
+    f32x16 accU[MI][2], accG[MI][2];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                accU[mi][ni][i] = 0.0f;
+                accG[mi][ni][i] = 0.0f;
+            }
+
+    const int l31 = lane & 31, lh = lane >> 5, sw = (l31 >> 1) & 3;
+    // byte addresses (inside a stage) of this lane's fragment rows, per k-step
+    uint32_t abase[2], bbase[2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+        const int ch = (2 * kk + lh) ^ sw;
+        abase[kk] = (uint32_t)(((wm * (32 * MI) + l31) * 4 + ch) * 16);
+        bbase[kk] = (uint32_t)((A_SLOTS + (wn * 64 + l31) * 4 + ch) * 16);
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void_t *)lds;   // LDS byte address of stage 0
+    u32x4 fa[2][MI], f1[2][2], fg[2][2];
+    constexpr int NREADS = MI + (GATED ? 4 : 2);
+    constexpr int NMFMA = MI * 2;                  // MFMA pairs (up, gate) or singles per k-step
+
+// read number r (0 .. NREADS-1) of fragment set F_ from stage address sa_/sb_
+#define FF1_READ_ONE(F_, r, sa_, sb_)                                                          \
+    {                                                                                          \
+        if ((r) < MI) FF1_DS_READ(fa[F_][(r) % MI], sa_, ((r) % MI) * 2048);                   \
+        else if ((r) < MI + 2) FF1_DS_READ(f1[F_][((r) - MI) % 2], sb_, (((r) - MI) % 2) * 2048); \
+        else FF1_DS_READ(fg[F_][((r) - MI) % 2], sb_, B_SLOTS * 16 + (((r) - MI) % 2) * 2048); \
+    }
+// MFMA(s) number m (0 .. NMFMA-1) of fragment set F_: tile (mi, ni) of the up product and, gated, of the gate product
+#define FF1_MFMA_ONE(F_, m)                                                                    \
+    {                                                                                          \
+        const int mi_ = (m) / 2, ni_ = (m) % 2;                                                \
+        accU[mi_][ni_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                              \
+            __builtin_bit_cast(bf16x8, fa[F_][mi_]), __builtin_bit_cast(bf16x8, f1[F_][ni_]), accU[mi_][ni_], 0, 0, 0); \
+        if (GATED)                                                                             \
+            accG[mi_][ni_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                          \
+                __builtin_bit_cast(bf16x8, fa[F_][mi_]), __builtin_bit_cast(bf16x8, fg[F_][ni_]), accG[mi_][ni_], 0, 0, 0); \
+    }
+#define FF1_WAIT_FRAGS(F_)                                                                     \
+    {                                                                                          \
+        if (MI == 4)                                                                           \
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(fa[F_][0]), "+v"(fa[F_][1]), "+v"(fa[F_][MI - 2]), "+v"(fa[F_][MI - 1]), \
+                         "+v"(f1[F_][0]), "+v"(f1[F_][1]), "+v"(fg[F_][0]), "+v"(fg[F_][1]));  \
+        else                                                                                   \
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(fa[F_][0]), "+v"(fa[F_][1]),            \
+                         "+v"(f1[F_][0]), "+v"(f1[F_][1]), "+v"(fg[F_][0]), "+v"(fg[F_][1]));  \
+    }
+
+    FF1_ISSUE(0)
+    FF1_ISSUE(1)
+    FF1_ISSUE(2)
+    __builtin_amdgcn_s_waitcnt(WAIT_TWO_TILES);      // tile 0 landed
+    FF1_BARRIER()
+    if (!GATED) {
+        fg[0][0] = fg[0][1] = fg[1][0] = fg[1][1] = (u32x4){0u, 0u, 0u, 0u};
+    }
+    {
+        const uint32_t sa = lds0 + abase[0], sb = lds0 + bbase[0];
+#pragma unroll
+        for (int r = 0; r < NREADS; ++r)
+            FF1_READ_ONE(0, r, sa, sb)
+    }
+    for (int kt = 0; kt < KT; ++kt) {
+        const uint32_t st_cur = lds0 + (uint32_t)((kt % NS) * STAGE * 16);
+        const uint32_t st_nxt = lds0 + (uint32_t)(((kt + 1) % NS) * STAGE * 16);
+        // ---- k-step 0 of tile kt; k-step 1's fragments are fetched underneath
+        FF1_WAIT_FRAGS(0)
+        {
+            const uint32_t sa = st_cur + abase[1], sb = st_cur + bbase[1];
+            FF1_PIN();
+#pragma unroll
+            for (int m = 0; m < NMFMA; ++m) {
+                if (m < NREADS)
+                    FF1_READ_ONE(1, m, sa, sb)
+                FF1_MFMA_ONE(0, m)
+                FF1_PIN();
+            }
+        }
+        // tile kt+1 has landed for this wave when only tile kt+2's loads are outstanding; past the
+        // barrier it has landed for every wave, and every wave is done reading tile kt-1, whose
+        // stage the loads of tile kt+3 overwrite
+        FF1_WAIT_FRAGS(1)
+        __builtin_amdgcn_s_waitcnt(WAIT_ONE_TILE);
+        FF1_BARRIER()
+        // ---- k-step 1; the first fragments of tile kt+1 and the loads of tile kt+3 go underneath
+        {
+            const uint32_t sa = st_nxt + abase[0], sb = st_nxt + bbase[0];
+            u32x4 *st_ = lds + ((kt + 3) % NS) * STAGE;
+            const int k0_ = min(kt + 3, KT - 1) * BK;
+            FF1_PIN();
+#pragma unroll
+            for (int m = 0; m < NMFMA; ++m) {
+                if (m < NREADS)
+                    FF1_READ_ONE(0, m, sa, sb)
+                if (m < AQ)
+                    __builtin_amdgcn_global_load_lds((gbl_cvoid_t *)(Xp + xoff[m % AQ] + k0_),
+                                                     (lds_void_t *)(st_ + (wave * AQ + (m % AQ)) * 64), 16, 0, 0);
+                else if (m < AQ + 2)
+                    __builtin_amdgcn_global_load_lds((gbl_cvoid_t *)(W1p + woff[(m - AQ) % 2] + k0_),
+                                                     (lds_void_t *)(st_ + A_SLOTS + (wave * 2 + (m - AQ) % 2) * 64), 16, 0, 0);
+                else if (GATED && m < AQ + 4)
+                    __builtin_amdgcn_global_load_lds((gbl_cvoid_t *)(Wgp + woff[(m - AQ) % 2] + k0_),
+                                                     (lds_void_t *)(st_ + A_SLOTS + B_SLOTS + (wave * 2 + (m - AQ) % 2) * 64), 16, 0, 0);
+                FF1_MFMA_ONE(1, m)
+                FF1_PIN();
+            }
+        }
+    }
+    FF1_WAIT_FRAGS(0)                                 // the reads issued for the tile past the end
+    __builtin_amdgcn_s_waitcnt(0x0F70);               // no LDS-DMA may outlive the loop
+    FF1_BARRIER()
+#undef FF1_ISSUE
+#undef FF1_BARRIER
+#undef FF1_DS_READ
+#undef FF1_PIN
+#undef FF1_READ_ONE
+#undef FF1_MFMA_ONE
+#undef FF1_WAIT_FRAGS
+
+    ff1_mfma_epilogue<ACT, GATED, MI>(p, accU, accG, rs, m0, n0, tile_n);
+}
+
+// ------------------------------------------------------------------------------------ bf16 / MFMA, register-staged
+// Fallback for d not a multiple of 32 (the k tail is zero-filled in registers, which the
+// direct-to-LDS loads cannot do): 16-byte global loads staged through VGPRs into two LDS
+// buffers of BK = 64.
+template <int ACT, bool GATED, int MI, bool KTAIL>
+__global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_staged_kernel(Ff1Params p)
 {
     constexpr int BM = 64 * MI;
     constexpr int AQ = BM / 32;      // 16-byte chunks of X a thread stages per k-tile
@@ -158,20 +425,16 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
     for (int kt = 0; kt < KT; ++kt) {
         const int buf = kt & 1;
         const bool more = kt + 1 < KT;
-#ifndef FF1_LAB_NOLOAD
         if (more)
             FF1_LOAD_TILE((kt + 1) * G_BK)
-#endif
         FF1_READ_FRAGS(1, buf, 1)
         FF1_MFMA(0)
         FF1_READ_FRAGS(0, buf, 2)
         FF1_MFMA(1)
         FF1_READ_FRAGS(1, buf, 3)
         FF1_MFMA(0)
-#ifndef FF1_LAB_NOSTORE
         if (more)
             FF1_STORE_TILE(buf ^ 1)
-#endif
         FF1_MFMA(1)
         __syncthreads();
         if (more)
@@ -183,57 +446,7 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
 #undef FF1_READ_FRAGS
 #undef FF1_MFMA
 
-#ifdef FF1_LAB_NOEPI
-    {
-        float s_ = 0.f;
-        for (int mi = 0; mi < MI; ++mi) for (int ni = 0; ni < 2; ++ni) for (int i = 0; i < 16; ++i) s_ += accU[mi][ni][i] + accG[mi][ni][i];
-        if (s_ == 1.2345f) p.Z[0] = s_;
-        return;
-    }
-#endif
-    // epilogue.  Lane holds column (neuron) l31 of each 32x32 tile and rows
-    // (i>>2)*8 + lh*4 + (i&3), i = 0..15.
-    float b1j[2], bgj[2];
-    int col[2];
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
-        col[ni] = n0 + wn * 64 + ni * 32 + l31;
-        const int cj = min(col[ni], p.F - 1);
-        b1j[ni] = p.b1 ? bf16_bits_to_f32(((const uint16_t *)p.b1)[cj]) : 0.0f;
-        bgj[ni] = (GATED && p.bg) ? bf16_bits_to_f32(((const uint16_t *)p.bg)[cj]) : 0.0f;
-    }
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int lrow = wm * (32 * MI) + mi * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
-            const int grow = m0 + lrow;
-            float sq = 0.0f;
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-                const float u = accU[mi][ni][i] + b1j[ni];
-                float z;
-                if (GATED)
-                    z = act_apply_t<ACT>(accG[mi][ni][i] + bgj[ni]) * u;
-                else
-                    z = act_apply_t<ACT>(u);
-                if (col[ni] < p.F) {
-                    sq = fmaf(z, z, sq);
-                    if (grow < p.M)
-                        p.Z[(int64_t)grow * p.ldz + col[ni]] = z;
-                }
-            }
-            // sum over the 32 lanes that share this row
-            sq = row16_sum(sq);
-            sq += __shfl_xor(sq, 16, 64);
-            if (l31 == 0)
-                rs[wn][lrow] = sq;
-        }
-    }
-    __syncthreads();
-    for (int r = tid; r < BM; r += G_THREADS)
-        if (m0 + r < p.M)
-            p.rowpart[(int64_t)(m0 + r) * p.nt + tile_n] = rs[0][r] + rs[1][r];
+    ff1_mfma_epilogue<ACT, GATED, MI>(p, accU, accG, rs, m0, n0, tile_n);
 }
 
 // ------------------------------------------------------------------------------------ fp32 / FMA
@@ -329,13 +542,13 @@ static void launch_mfma(const Ff1Params &p, bool gated, hipStream_t st)
 {
     const int nblk = p.mt * p.nt;
     dim3 grid(((nblk + 7) / 8) * 8), block(G_THREADS);
-    const bool ktail = p.d % G_BK != 0;
+    const bool ktail = p.d % 32 != 0;
     if (gated) {
-        if (ktail) hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, true, MI, true>), grid, block, 0, st, p);
-        else hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, true, MI, false>), grid, block, 0, st, p);
+        if (ktail) hipLaunchKernelGGL((ff1_bf16_mfma_staged_kernel<ACT, true, MI, true>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, true, MI>), grid, block, 0, st, p);
     } else {
-        if (ktail) hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, false, MI, true>), grid, block, 0, st, p);
-        else hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, false, MI, false>), grid, block, 0, st, p);
+        if (ktail) hipLaunchKernelGGL((ff1_bf16_mfma_staged_kernel<ACT, false, MI, true>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, false, MI>), grid, block, 0, st, p);
     }
 }
 
