@@ -41,14 +41,16 @@ __device__ __forceinline__ void store_scalar(void *p, int64_t i, float v)
 }
 
 // ------------------------------------------------------------------ sigma of Eq. 2 / Eq. 3
-__device__ __forceinline__ float act_silu(float a) { return a / (1.0f + __expf(-a)); }
+// silu(a) = a * sigmoid(a); tanh-GELU(a) = 0.5 a (1 + tanh(u)) = a * sigmoid(2u) with
+// u = sqrt(2/pi) (a + 0.044715 a^3).  One v_exp_f32 and one v_rcp_f32 (1 ulp) each.
+__device__ __forceinline__ float fast_sigmoid(float v) { return __builtin_amdgcn_rcpf(1.0f + __expf(-v)); }
+
+__device__ __forceinline__ float act_silu(float a) { return a * fast_sigmoid(a); }
 
 __device__ __forceinline__ float act_gelu_tanh(float a)
 {
-    // 0.5 a (1 + tanh(u)),  tanh(u) = 1 - 2 / (exp(2u) + 1)
-    float u = 0.7978845608028654f * (a + 0.044715f * a * a * a);
-    float t = 1.0f - 2.0f / (__expf(2.0f * u) + 1.0f);
-    return 0.5f * a * (1.0f + t);
+    const float u2 = 1.5957691216057308f * (a + 0.044715f * a * a * a);
+    return a * fast_sigmoid(u2);
 }
 
 __device__ __forceinline__ float act_apply(int act, float a)

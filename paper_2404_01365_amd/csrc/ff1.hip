@@ -69,7 +69,7 @@ __device__ __forceinline__ void ff1_mfma_epilogue(const Ff1Params &p, f32x16 (&a
                 if (col[ni] < p.F) {
                     sq = fmaf(z, z, sq);
                     if (grow < p.M)
-                        p.Z[(int64_t)grow * p.ldz + col[ni]] = z;
+                        __builtin_nontemporal_store(z, &p.Z[(int64_t)grow * p.ldz + col[ni]]);
                 }
             }
             // sum over the 32 lanes that share this row
