@@ -27,7 +27,7 @@ def boundary_report(s: np.ndarray, k: int) -> Tuple[float, float]:
 
 def open_margin(Xs: Sequence[np.ndarray], Wg, W1: np.ndarray, act: int, dtype: int, ks: Sequence[int],
                 bg=None, b1=None, target: float = 2e-3, band: float = 4e-3, factor: float = 0.98,
-                max_iter: int = 16, Zs: List[np.ndarray] = None, verbose: bool = False):
+                max_iter: int = 64, Zs: List[np.ndarray] = None, verbose: bool = False):
     """Nudge W1 in place until every (sequence, k) boundary has a relative gap >= target.
 
     Returns (nudges, s_list): the (row, factor) pairs in application order and the final
