@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="layers to run (default: all of the config)")
     ap.add_argument("--probe-every", type=int, default=8, help="decode steps between kernel-duration probes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--skip-full-width", action="store_true",
+                    help="do not time the full-width block after the timed region (keeps a profile's per-kernel "
+                         "averages to the pruned launches only)")
     ap.add_argument("--warm", action="store_true", help="single copy of the compact weights (cache-warm)")
     return ap.parse_args()
 
@@ -211,15 +214,17 @@ def main():
     # timed region: decode latency of the pruned block relative to the full one
     ws_full = torch.empty(G.griffin_decode_workspace_bytes(d, F, 1), dtype=torch.uint8, device="cuda")
     fe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    for rep in range(2):
+    for rep in range(0 if args.skip_full_width else 2):
         if rep == 1:
             fe[0].record()
         for tok in range(T):
             for t in layers:
                 G.griffin_ff_decode(t["L"], t["xp"] + tok * esz, t["yp"] + tok * esz, 1, workspace=ws_full, stream=stream)
-    fe[1].record()
-    torch.cuda.synchronize()
-    full_us = fe[0].elapsed_time(fe[1]) * 1e3 / (T * n_layers)
+    full_us = None
+    if not args.skip_full_width:
+        fe[1].record()
+        torch.cuda.synchronize()
+        full_us = fe[0].elapsed_time(fe[1]) * 1e3 / (T * n_layers)
 
     ms_per_step = wall * 1e3 / args.steps
     sel_ms = sum(e[0].elapsed_time(e[1]) for e in stage_ev) / len(stage_ev)
@@ -276,7 +281,7 @@ def main():
             "us_per_layer_token": dec_ms * 1e3 / (T * n_layers),
             "GBps_per_layer_token": alg_bytes / (dec_ms * 1e-3 / (T * n_layers)) / 1e9,
             "full_width_us_per_layer_token": full_us,
-            "pruned_over_full_latency": u / full_us,
+            "pruned_over_full_latency": (u / full_us) if full_us else None,
         },
         "select_us_per_layer": sel_ms * 1e3 / n_layers,
     }
