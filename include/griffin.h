@@ -129,7 +129,9 @@ int griffin_compact(const griffin_layer *L, const int32_t *idx, int32_t k,
  * Generation phase (Section 4.2, "Generation with Expert Neurons"; Eq. 4-5):
  *   z = sigma(Wg x + bg) * (W1 x + b1),   y = sum_j z_j W2[j][:] + b2
  * for `batch` independent rows x[b] through the ONE block C (a compact block, or a full one
- * with n = D_FF, which is Eq. 1).  x, y: [batch][d] contiguous, C->dtype.
+ * with n = D_FF, which is Eq. 1).  x, y: [batch][d] contiguous, C->dtype.  With batch > 1 the
+ * rows share one selected set (Section 5.3, Eq. 7) and the weights are streamed once per
+ * four rows.
  * workspace >= griffin_decode_workspace_bytes(d, n, batch) bytes, 256-byte aligned.
  */
 size_t griffin_decode_workspace_bytes(int32_t d, int32_t n, int32_t batch);

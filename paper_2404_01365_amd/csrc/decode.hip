@@ -27,6 +27,7 @@ namespace griffin {
 constexpr int DEC_G = 1;                 // neurons per team step
 constexpr int DEC_MAX_WAVES = 16;        // waves per workgroup
 constexpr int DEC_MAX_PARTS = 256;       // partial rows per batch row
+constexpr int DEC_NB_MAX = 4;            // rows of x sharing one pass over the weights
 constexpr int DEC_FOLD_FLOATS = 8192;    // LDS floats for folding teams (d <= 8192)
 
 struct DecodeParams {
@@ -35,7 +36,7 @@ struct DecodeParams {
     const void *x;
     float *part;
     int64_t ld;
-    int32_t d, n, n_src, act, P;
+    int32_t d, n, n_src, act, P, batch;
     int32_t R, teams;        // waves per team, teams per workgroup
 };
 
@@ -86,10 +87,12 @@ struct Chunk {
 // GATED and INDEXED are compile-time so that the three row loads of a neuron are issued
 // back to back with no branch between them (a branch there makes the compiler wait for the
 // first load before issuing the next).
-template <bool BF16, bool GATED, bool INDEXED, bool BIAS>
+// NB = rows of x that share the block's weights in one pass (the weights are streamed once for
+// NB rows; 1 for the per-row variants).
+template <bool BF16, bool GATED, bool INDEXED, bool BIAS, int NB>
 __device__ __forceinline__ void decode_body(const DecodeParams &p, const void *Wg, const void *W1,
                                             const void *W2, const void *bg, const void *b1,
-                                            float (*red)[2 * DEC_G][16], float *fold)
+                                            float (*red)[2 * DEC_G * DEC_NB_MAX][16], float *fold)
 {
     constexpr int E = Chunk<BF16>::E;
     constexpr int ES = BF16 ? 2 : 4;
@@ -98,29 +101,34 @@ __device__ __forceinline__ void decode_body(const DecodeParams &p, const void *W
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, in an SGPR
     const int R = p.R;
     const int team = wave / R, wt = wave - team * R;
-    const int b = blockIdx.y;
+    const int b = blockIdx.y * NB;           // first of this block's NB rows
     const int d = p.d, nch = d / E;
 
     const int c = wt * 64 + lane;            // this lane's 16-byte chunk of every row
     const bool valid = c < nch;
     const int cc = valid ? c : nch - 1;      // clamped: loads stay in bounds, x = 0 kills the terms
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    const u32x4 xr = valid ? ((const u32x4 *)((const char *)p.x + (int64_t)b * d * ES))[cc] : zero4;
-
-    float ya[8];
+    u32x4 xr[NB];
+    float ya[NB][8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-        ya[e] = 0.0f;
+    for (int nb = 0; nb < NB; ++nb) {
+        const bool live = valid && b + nb < p.batch;     // rows past the batch behave as x = 0
+        xr[nb] = live ? ((const u32x4 *)((const char *)p.x + (int64_t)(b + nb) * d * ES))[cc] : zero4;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            ya[nb][e] = 0.0f;
+    }
 
     const int NT = gridDim.x * p.teams;              // teams on the chip for this batch row
     const int T = blockIdx.x * p.teams + team;
     const int nsteps = (p.n + NT * G - 1) / (NT * G);
     const int32_t *idx = INDEXED ? p.idx + (int64_t)b * p.n : nullptr;
     const int64_t row_bytes = p.ld * ES;
-    float(*myred)[2 * G][16] = red + team * 2;       // [parity][value][wave of the team]
+    constexpr int NV = 2 * G * NB;                   // values to combine across the team per step
+    float(*myred)[2 * G * DEC_NB_MAX][16] = red + team * 2;   // [parity][value][wave of the team]
 
     // zero the padding entries of the cross-wave buffers once
-    for (int i = threadIdx.x; i < p.teams * 2 * 2 * G * 16; i += blockDim.x)
+    for (int i = threadIdx.x; i < p.teams * 2 * 2 * G * DEC_NB_MAX * 16; i += blockDim.x)
         (&red[0][0][0])[i] = 0.0f;
     __syncthreads();
 
@@ -155,30 +163,38 @@ __device__ __forceinline__ void decode_body(const DecodeParams &p, const void *W
 
 #define DEC_CONSUME(B_, s_)                                                                  \
     {                                                                                        \
-        float pv_[2 * G];                                                                    \
-        _Pragma("unroll") for (int g = 0; g < G; ++g)                                        \
+        float pv_[NV];                                                                       \
+        _Pragma("unroll") for (int nb = 0; nb < NB; ++nb)                                    \
+            _Pragma("unroll") for (int g = 0; g < G; ++g)                                    \
         {                                                                                    \
-            pv_[2 * g] = GATED ? wave_sum(Chunk<BF16>::dot(buf[B_][g][0], xr)) : 0.0f;       \
-            pv_[2 * g + 1] = wave_sum(Chunk<BF16>::dot(buf[B_][g][1], xr));                  \
+            pv_[(nb * G + g) * 2] = GATED ? wave_sum(Chunk<BF16>::dot(buf[B_][g][0], xr[nb])) : 0.0f; \
+            pv_[(nb * G + g) * 2 + 1] = wave_sum(Chunk<BF16>::dot(buf[B_][g][1], xr[nb]));   \
         }                                                                                    \
         if (lane == 0) {                                                                     \
-            _Pragma("unroll") for (int v = 0; v < 2 * G; ++v) myred[(s_) & 1][v][wt] = pv_[v]; \
+            _Pragma("unroll") for (int v = 0; v < NV; ++v) myred[(s_) & 1][v][wt] = pv_[v];  \
         }                                                                                    \
         __syncthreads();                                                                     \
-        float q_ = lane < 2 * G * 16 ? myred[(s_) & 1][lane >> 4][lane & 15] : 0.0f;         \
-        q_ = row16_sum(q_);                                                                  \
-        _Pragma("unroll") for (int g = 0; g < G; ++g)                                        \
+        _Pragma("unroll") for (int q = 0; q < (NV + 3) / 4; ++q)                             \
         {                                                                                    \
-            const int j_ = ((s_) * NT + T) * G + g;                                          \
-            float gg_ = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(q_), 32 * g));      \
-            float uu_ = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(q_), 32 * g + 16)); \
-            if (BIAS) {                                                                      \
-                gg_ += bias[B_][g][0];                                                       \
-                uu_ += bias[B_][g][1];                                                       \
+            float q_ = q * 4 + (lane >> 4) < NV ? myred[(s_) & 1][q * 4 + (lane >> 4)][lane & 15] : 0.0f; \
+            q_ = row16_sum(q_);                                                              \
+            _Pragma("unroll") for (int h = 0; h < 2; ++h)                                    \
+            {                                                                                \
+                if (q * 4 + 2 * h < NV) {                                                    \
+                    const int pair_ = q * 2 + h;         /* = nb * G + g */                  \
+                    const int nb_ = pair_ / G, g_ = pair_ % G;                               \
+                    const int j_ = ((s_) * NT + T) * G + g_;                                 \
+                    float gg_ = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(q_), 32 * h));      \
+                    float uu_ = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(q_), 32 * h + 16)); \
+                    if (BIAS) {                                                              \
+                        gg_ += bias[B_][g_][0];                                              \
+                        uu_ += bias[B_][g_][1];                                              \
+                    }                                                                        \
+                    float z_ = GATED ? act_apply(p.act, gg_) * uu_ : act_apply(p.act, uu_);  \
+                    z_ = j_ < p.n ? z_ : 0.0f;                                               \
+                    Chunk<BF16>::axpy(z_, buf[B_][g_][2], ya[nb_]);                          \
+                }                                                                            \
             }                                                                                \
-            float z_ = GATED ? act_apply(p.act, gg_) * uu_ : act_apply(p.act, uu_);          \
-            z_ = j_ < p.n ? z_ : 0.0f;                                                       \
-            Chunk<BF16>::axpy(z_, buf[B_][g][2], ya);                                        \
         }                                                                                    \
     }
 
@@ -204,46 +220,49 @@ __device__ __forceinline__ void decode_body(const DecodeParams &p, const void *W
 #undef DEC_CONSUME
     (void)rows;
 
-    // fold the workgroup's teams (fixed order), then one fp32 partial row per workgroup
-    for (int t = 1; t < p.teams; ++t) {
-        if (team == t && valid) {
+    // fold the workgroup's teams (fixed order), then one fp32 partial row per workgroup and x row
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        for (int t = 1; t < p.teams; ++t) {
+            if (team == t && valid) {
+#pragma unroll
+                for (int e = 0; e < E; e += 4)
+                    *(float4 *)(fold + c * E + e) = make_float4(ya[nb][e], ya[nb][e + 1], ya[nb][e + 2], ya[nb][e + 3]);
+            }
+            __syncthreads();
+            if (team == 0 && valid) {
+#pragma unroll
+                for (int e = 0; e < E; e += 4) {
+                    const float4 v = *(const float4 *)(fold + c * E + e);
+                    ya[nb][e] += v.x; ya[nb][e + 1] += v.y; ya[nb][e + 2] += v.z; ya[nb][e + 3] += v.w;
+                }
+            }
+            __syncthreads();
+        }
+        if (team == 0 && valid && b + nb < p.batch) {
+            float *out = p.part + ((int64_t)(b + nb) * p.P + blockIdx.x) * d + c * E;
 #pragma unroll
             for (int e = 0; e < E; e += 4)
-                *(float4 *)(fold + c * E + e) = make_float4(ya[e], ya[e + 1], ya[e + 2], ya[e + 3]);
+                *(float4 *)(out + e) = make_float4(ya[nb][e], ya[nb][e + 1], ya[nb][e + 2], ya[nb][e + 3]);
         }
-        __syncthreads();
-        if (team == 0 && valid) {
-#pragma unroll
-            for (int e = 0; e < E; e += 4) {
-                const float4 v = *(const float4 *)(fold + c * E + e);
-                ya[e] += v.x; ya[e + 1] += v.y; ya[e + 2] += v.z; ya[e + 3] += v.w;
-            }
-        }
-        __syncthreads();
-    }
-    if (team == 0 && valid) {
-        float *out = p.part + ((int64_t)b * p.P + blockIdx.x) * d + c * E;
-#pragma unroll
-        for (int e = 0; e < E; e += 4)
-            *(float4 *)(out + e) = make_float4(ya[e], ya[e + 1], ya[e + 2], ya[e + 3]);
     }
 }
 
-template <bool BF16, bool GATED, bool INDEXED, bool BIAS>
+template <bool BF16, bool GATED, bool INDEXED, bool BIAS, int NB>
 __global__ __launch_bounds__(DEC_MAX_WAVES * 64) void ff_decode_kernel(DecodeParams p)
 {
-    __shared__ float red[DEC_MAX_WAVES * 2][2 * DEC_G][16];
+    __shared__ float red[DEC_MAX_WAVES * 2][2 * DEC_G * DEC_NB_MAX][16];
     __shared__ __attribute__((aligned(16))) float fold[DEC_FOLD_FLOATS];
-    decode_body<BF16, GATED, INDEXED, BIAS>(p, p.Wg, p.W1, p.W2, p.bg, p.b1, red, fold);
+    decode_body<BF16, GATED, INDEXED, BIAS, NB>(p, p.Wg, p.W1, p.W2, p.bg, p.b1, red, fold);
 }
 
 template <bool BF16, bool GATED, bool BIAS>
 __global__ __launch_bounds__(DEC_MAX_WAVES * 64) void ff_decode_multi_kernel(DecodeParams p, MultiPtrs m)
 {
-    __shared__ float red[DEC_MAX_WAVES * 2][2 * DEC_G][16];
+    __shared__ float red[DEC_MAX_WAVES * 2][2 * DEC_G * DEC_NB_MAX][16];
     __shared__ __attribute__((aligned(16))) float fold[DEC_FOLD_FLOATS];
     const void *const *q = m.p[blockIdx.y];
-    decode_body<BF16, GATED, false, BIAS>(p, q[0], q[1], q[2], q[3], q[4], red, fold);
+    decode_body<BF16, GATED, false, BIAS, 1>(p, q[0], q[1], q[2], q[3], q[4], red, fold);
 }
 
 struct B2Ptrs {
@@ -298,12 +317,13 @@ static int decode_team_waves(int32_t d, bool bf16)
     return (R <= DEC_MAX_WAVES && d <= DEC_FOLD_FLOATS) ? R : 0;
 }
 
-// workgroups (= partial rows) per batch row
+// workgroups (= partial rows) per batch row: enough to fill the chip when the rows of a batch
+// are taken DEC_NB_MAX at a time
 int decode_parts(int32_t n, int32_t batch)
 {
-    int P = (512 + batch - 1) / batch;
+    const int groups = batch <= 2 ? 1 : (batch + DEC_NB_MAX - 1) / DEC_NB_MAX;
+    int P = (512 + groups - 1) / groups;
     if (P > DEC_MAX_PARTS) P = DEC_MAX_PARTS;
-
     if (P < 8) P = 8;
     const int by_work = (n + 2 * DEC_G - 1) / (2 * DEC_G);
     if (P > by_work) P = by_work;
@@ -333,7 +353,7 @@ int launch_decode(const DecodeJob &job, hipStream_t st)
     p.Wg = job.Wg; p.W1 = job.W1; p.W2 = job.W2; p.bg = job.bg; p.b1 = job.b1;
     p.idx = job.idx; p.n_src = job.idx ? job.n_src : job.n;
     p.x = job.x; p.part = job.part; p.ld = job.ld;
-    p.d = job.d; p.n = job.n; p.act = job.act; p.P = P;
+    p.d = job.d; p.n = job.n; p.act = job.act; p.P = P; p.batch = job.batch;
     p.R = R;
     // about eight waves per workgroup, one workgroup per CU: measured best (more waves or
     // more loads in flight per CU lower the achieved bandwidth)
@@ -360,13 +380,22 @@ int launch_decode(const DecodeJob &job, hipStream_t st)
     if (ev_begin && hipEventRecord(ev_begin, st) != hipSuccess)
         return set_hip_error(hipGetLastError(), "hipEventRecord");
 
-    dim3 grid(P, job.batch), block(p.teams * R * 64);
+    // rows through one shared block are taken NB at a time (weights streamed once per NB rows)
+    const bool shared_block = !job.multi && !job.idx;
+    const int NB = !shared_block || job.batch == 1 ? 1 : (job.batch == 2 ? 2 : DEC_NB_MAX);
+    dim3 grid(P, (job.batch + NB - 1) / NB), block(p.teams * R * 64);
     const bool gated = job.multi ? job.multi[0].Wg != nullptr : job.Wg != nullptr;
     const bool indexed = job.idx != nullptr;
     const bool bias = job.multi ? (job.multi[0].bg || job.multi[0].b1) : (job.bg || job.b1);
-#define DEC_GO(BF, GA, IX, BI) hipLaunchKernelGGL((ff_decode_kernel<BF, GA, IX, BI>), grid, block, 0, st, p)
+#define DEC_GO1(BF, GA, IX, BI, NB_) hipLaunchKernelGGL((ff_decode_kernel<BF, GA, IX, BI, NB_>), grid, block, 0, st, p)
+#define DEC_GO(BF, GA, IX, BI)                                         \
+    {                                                                  \
+        if (IX || NB == 1) DEC_GO1(BF, GA, IX, BI, 1);                 \
+        else if (NB == 2) DEC_GO1(BF, GA, false, BI, 2);               \
+        else DEC_GO1(BF, GA, false, BI, DEC_NB_MAX);                   \
+    }
 #define DEC_GO_MULTI(BF, GA, BI) hipLaunchKernelGGL((ff_decode_multi_kernel<BF, GA, BI>), grid, block, 0, st, p, m)
-#define DEC_PICK3(BF, GA, IX) { if (bias) DEC_GO(BF, GA, IX, true); else DEC_GO(BF, GA, IX, false); }
+#define DEC_PICK3(BF, GA, IX) { if (bias) DEC_GO(BF, GA, IX, true) else DEC_GO(BF, GA, IX, false) }
 #define DEC_PICK2(BF, GA) { if (indexed) DEC_PICK3(BF, GA, true) else DEC_PICK3(BF, GA, false) }
 #define DEC_PICKM(BF, GA) { if (bias) DEC_GO_MULTI(BF, GA, true); else DEC_GO_MULTI(BF, GA, false); }
     if (job.multi) {
@@ -381,6 +410,7 @@ int launch_decode(const DecodeJob &job, hipStream_t st)
 #undef DEC_PICK2
 #undef DEC_PICKM
 #undef DEC_GO
+#undef DEC_GO1
 #undef DEC_GO_MULTI
     int rc = check_launch("ff_decode_kernel");
     if (rc != GRIFFIN_OK)

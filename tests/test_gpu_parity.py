@@ -68,17 +68,25 @@ def test_ff_decode_matches_oracle(dtype, d, n, act, gated, bias):
         assert max_rel(got, ref) <= TOL_OUT[dtype], (dtype, d, n, t)
 
 
-def test_ff_decode_batch_rows_are_independent():
-    dtype, d, n = synth.DT_BF16, 1024, 300
-    c = synth.small_case(5, d, n, 4, dtype, T=5)
-    L, _ = dev_layer(c["Wg"], c["W1"], c["W2"], synth.ACT_SILU, dtype)
+@pytest.mark.parametrize("dtype,d,n,batch,bias", [
+    (synth.DT_BF16, 1024, 300, 5, False),     # 4 rows per pass + a ragged group
+    (synth.DT_BF16, 4096, 96, 2, True),       # 2 rows per pass
+    (synth.DT_BF16, 3072, 130, 16, False),
+    (synth.DT_F32, 264, 77, 7, True),
+])
+def test_ff_decode_batch_shares_one_block(dtype, d, n, batch, bias):
+    c = synth.small_case(5 + batch, d, n, 4, dtype, T=batch, with_bias=bias)
+    L, _ = dev_layer(c["Wg"], c["W1"], c["W2"], synth.ACT_SILU, dtype, c.get("bg"), c.get("b1"), c.get("b2"))
     x = to_dev(c["xt"], dtype)
-    got = run_decode(L, x, batch=5)
-    for t in range(5):
-        ref = oracle.ff_decode(c["xt"][t], c["Wg"], c["W1"], c["W2"], synth.ACT_SILU)
-        assert max_rel(got[t], ref) <= TOL_OUT[dtype]
+    got = run_decode(L, x, batch=batch)
+    for t in range(batch):
+        ref = oracle.ff_decode(c["xt"][t], c["Wg"], c["W1"], c["W2"], synth.ACT_SILU, c.get("bg"), c.get("b1"), c.get("b2"))
+        assert max_rel(got[t], ref) <= TOL_OUT[dtype], t
+        # a row alone gives the same result up to the order of the fp32 partial sums (the
+        # number of partial rows depends on the batch size)
+        assert max_rel(got[t], run_decode(L, x[t:t + 1].contiguous(), batch=1)[0]) <= (2.0 ** -7 if dtype == synth.DT_BF16 else 1e-6)
     # deterministic: a second run gives the same bits
-    assert np.array_equal(got, run_decode(L, x, batch=5))
+    assert np.array_equal(got, run_decode(L, x, batch=batch))
 
 
 # ------------------------------------------------------------------ compaction
