@@ -90,7 +90,7 @@ __device__ __forceinline__ void ff1_mfma_epilogue(const Ff1Params &p, f32x16 (&a
 // (global_load_lds_dwordx4: lane l of a wave instruction fills 16-byte slot l of a 1 KB region,
 // no VGPR staging, no ds_write), BK = 32, four LDS stages, so three k-tiles (~3000 MFMA
 // cycles) of loads are in flight.  A row of a stage is 64 B = 4 slots; logical chunk c of row r
-// sits in slot c ^ ((r >> 1) & 3), which keeps the ds_read_b128 operand fetches conflict-free;
+// sits in slot c ^ ((r >> 2) & 3), which keeps the ds_read_b128 operand fetches conflict-free;
 // the swizzle is applied by choosing which global chunk each lane loads.  The loop body is
 // branch-free (loads past the last k-tile re-read the last one into a dead stage) so that the
 // scheduler can interleave LDS reads and loads between MFMAs: k-step 1's fragments are read
@@ -133,12 +133,12 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
 #pragma unroll
     for (int q = 0; q < AQ; ++q) {
         const int row = (wave * AQ + q) * 16 + lrow;
-        xoff[q] = (int64_t)min(m0 + row, p.M - 1) * p.ldx + (lp ^ ((row >> 1) & 3)) * 8;
+        xoff[q] = (int64_t)min(m0 + row, p.M - 1) * p.ldx + (lp ^ ((row >> 2) & 3)) * 8;
     }
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
         const int row = (wave * 2 + q) * 16 + lrow;
-        woff[q] = (int64_t)min(n0 + row, p.F - 1) * p.ldw + (lp ^ ((row >> 1) & 3)) * 8;
+        woff[q] = (int64_t)min(n0 + row, p.F - 1) * p.ldw + (lp ^ ((row >> 2) & 3)) * 8;
     }
     const uint16_t *Xp = (const uint16_t *)p.X, *W1p = (const uint16_t *)p.W1, *Wgp = (const uint16_t *)p.Wg;
     const int KT = p.d / BK;
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
                 accG[mi][ni][i] = 0.0f;
             }
 
-    const int l31 = lane & 31, lh = lane >> 5, sw = (l31 >> 1) & 3;
+    const int l31 = lane & 31, lh = lane >> 5, sw = (l31 >> 2) & 3;
     // byte addresses (inside a stage) of this lane's fragment rows, per k-step
     uint32_t abase[2], bbase[2];
 #pragma unroll
