@@ -197,6 +197,7 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
     u32x4 fa[2][MI], f1[2][2], fg[2][2];
     constexpr int NREADS = MI + (GATED ? 4 : 2);
     constexpr int NMFMA = MI * 2;                  // MFMA pairs (up, gate) or singles per k-step
+    constexpr int NSLOTS = NMFMA > NREADS ? NMFMA : NREADS;   // interleaving slots per k-step (NLOADS == NREADS)
 
 // read number r (0 .. NREADS-1) of fragment set F_ from stage address sa_/sb_
 #define FF1_READ_ONE(F_, r, sa_, sb_)                                                          \
@@ -248,10 +249,11 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
             const uint32_t sa = st_cur + abase[1], sb = st_cur + bbase[1];
             FF1_PIN();
 #pragma unroll
-            for (int m = 0; m < NMFMA; ++m) {
+            for (int m = 0; m < NSLOTS; ++m) {
                 if (m < NREADS)
                     FF1_READ_ONE(1, m, sa, sb)
-                FF1_MFMA_ONE(0, m)
+                if (m < NMFMA)
+                    FF1_MFMA_ONE(0, m)
                 FF1_PIN();
             }
         }
@@ -268,7 +270,7 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
             const int k0_ = min(kt + 3, KT - 1) * BK;
             FF1_PIN();
 #pragma unroll
-            for (int m = 0; m < NMFMA; ++m) {
+            for (int m = 0; m < NSLOTS; ++m) {
                 if (m < NREADS)
                     FF1_READ_ONE(0, m, sa, sb)
                 if (m < AQ)
@@ -280,7 +282,8 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
                 else if (GATED && m < AQ + 4)
                     __builtin_amdgcn_global_load_lds((gbl_cvoid_t *)(Wgp + woff[(m - AQ) % 2] + k0_),
                                                      (lds_void_t *)(st_ + A_SLOTS + B_SLOTS + (wave * 2 + (m - AQ) % 2) * 64), 16, 0, 0);
-                FF1_MFMA_ONE(1, m)
+                if (m < NMFMA)
+                    FF1_MFMA_ONE(1, m)
                 FF1_PIN();
             }
         }

@@ -56,6 +56,9 @@ def run_decode(C, x_dev, batch=1):
     (synth.DT_BF16, 3072, 257, synth.ACT_RELU, True, False),
     (synth.DT_BF16, 5120, 130, synth.ACT_SILU, False, True),      # widest register tiling in use
     (synth.DT_BF16, 6144, 64, synth.ACT_SILU, True, False),
+    (synth.DT_BF16, 8192, 40, synth.ACT_GELU_TANH, True, True),   # widest row this build covers
+    (synth.DT_BF16, 8, 5, synth.ACT_SILU, True, False),           # one 16-byte chunk per row
+    (synth.DT_F32, 4096, 33, synth.ACT_SILU, True, False),        # 16 waves per team
 ])
 def test_ff_decode_matches_oracle(dtype, d, n, act, gated, bias):
     c = synth.small_case(d * 7 + n, d, n, 4, dtype, T=3, with_bias=bias)
@@ -190,6 +193,9 @@ PREFILL_CASES = [
     (synth.DT_BF16, 512, 1000, [300], 500, synth.ACT_SILU, True, False),         # 3 x 8 tiles, ragged both
     (synth.DT_BF16, 136, 260, [129, 0, 200], 77, synth.ACT_GELU_TANH, True, True),  # k tail, empty seq
     (synth.DT_BF16, 256, 384, [256], 100, synth.ACT_RELU, False, False),         # Eq. 2 on the MFMA path
+    (synth.DT_BF16, 64, 131, [1, 2, 130], 7, synth.ACT_SILU, True, False),       # one-token prompts, D_ff odd, KT = 2
+    (synth.DT_BF16, 32, 40, [5], 40, synth.ACT_GELU_TANH, True, True),           # a single k-tile, keep all
+    (synth.DT_BF16, 1024, 2500, [700], 1, synth.ACT_SILU, True, False),          # k = 1, three 256-token tiles
 ]
 
 
