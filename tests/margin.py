@@ -27,11 +27,14 @@ def boundary_report(s: np.ndarray, k: int) -> Tuple[float, float]:
 
 def open_margin(Xs: Sequence[np.ndarray], Wg, W1: np.ndarray, act: int, dtype: int, ks: Sequence[int],
                 bg=None, b1=None, target: float = 2e-3, band: float = 4e-3, factor: float = 0.98,
-                max_iter: int = 64, Zs: List[np.ndarray] = None, verbose: bool = False):
+                max_iter: int = 64, Zs: List[np.ndarray] = None, verbose: bool = False, combine=None):
     """Nudge W1 in place until every (sequence, k) boundary has a relative gap >= target.
 
     Returns (nudges, s_list): the (row, factor) pairs in application order and the final
     statistic of every sequence.  `Zs` may pass precomputed oracle activations per sequence.
+    `combine` maps the list of per-sequence statistics to the list of score vectors whose
+    top-k boundaries must be clear (default: the statistics themselves); it is how a batch
+    that shares one set (Eq. 7) gets its margin on the shared score.
     """
     F = W1.shape[0]
     if Zs is None:
@@ -41,7 +44,7 @@ def open_margin(Xs: Sequence[np.ndarray], Wg, W1: np.ndarray, act: int, dtype: i
         s_list = [oracle.stat(Z) for Z in Zs]
         rows = set()
         worst = float("inf")
-        for s in s_list:
+        for s in (combine(s_list) if combine else s_list):
             order = np.argsort(-s, kind="stable")
             for k in ks:
                 if k >= F:

@@ -264,3 +264,41 @@ def test_config0_end_to_end():
         assert max_rel(got, ref) <= TOL_OUT[cfg.dtype]
         full = oracle.ff_decode(xt[step], Wg, W1, W2, cfg.act)
         assert max_rel(run_decode(L, to_dev(xt[step], cfg.dtype)), full) <= TOL_OUT[cfg.dtype]
+
+
+# ------------------------------------------------------------------ one shared set for a batch (Eq. 7)
+def test_shared_set_for_a_batch_end_to_end():
+    """Section 5.3: the samples of a batch are aggregated with s_bar = sum_b s_b / sqrt(S_b), one
+    set is selected and every row decodes through the same compact block."""
+    dtype, d, F, k, act = synth.DT_BF16, 512, 1200, 600, synth.ACT_SILU
+    lens = [40, 170, 90, 300, 64]
+    B = len(lens)
+    c = synth.small_case(4242, d, F, sum(lens), dtype, T=B)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    Xs = [c["X"][cu[b]:cu[b + 1]] for b in range(B)]
+    W1 = c["W1"].copy()
+    shared = lambda s_list: [oracle.stat_shared(np.stack(s_list), np.array(lens))]
+    _, s_list = open_margin(Xs, c["Wg"], W1, act, dtype, [k], combine=shared)
+    sbar_ref = shared(s_list)[0]
+    assert boundary_report(sbar_ref, k)[0] > 1e-3
+    idx_ref = oracle.topk(sbar_ref, k)
+
+    L, t = dev_layer(c["Wg"], W1, c["W2"], act, dtype)
+    idx_seq = torch.empty((B, k), dtype=torch.int32, device="cuda")
+    s_dev = torch.empty((B, F), dtype=torch.float32, device="cuda")
+    ws = workspace(G.griffin_prefill_workspace_bytes(L, int(cu[-1]), B, False))
+    G.griffin_prefill_select(L, to_dev(c["X"], dtype), [int(v) for v in cu], k, idx_seq, s_out=s_dev, workspace=ws)
+    sbar = torch.empty((F,), dtype=torch.float32, device="cuda")
+    G.griffin_stat_shared(s_dev, [int(v) for v in cu], sbar)
+    idx = torch.empty((1, k), dtype=torch.int32, device="cuda")
+    G.griffin_topk(sbar, k, idx)
+    sync()
+    assert max_rel(sbar.cpu().numpy(), sbar_ref) <= TOL_S
+    np.testing.assert_array_equal(idx.cpu().numpy()[0], idx_ref)
+
+    C, _ = empty_compact(L, k, t, interleaved=True)
+    G.griffin_compact(L, idx, k, C)
+    got = run_decode(C, to_dev(c["xt"], dtype), batch=B)
+    cw = [oracle.compact(w, idx_ref) for w in (c["Wg"], W1, c["W2"])]
+    for b in range(B):
+        assert max_rel(got[b], oracle.ff_decode(c["xt"][b], *cw, act)) <= TOL_OUT[dtype]
