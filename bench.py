@@ -226,6 +226,25 @@ def main():
         torch.cuda.synchronize()
         full_us = fe[0].elapsed_time(fe[1]) * 1e3 / (T * n_layers)
 
+    # the prompt's own full-width output Y = Z W_2^T (Section 5.1), outside the timed region
+    prompt_out_us = None
+    if not args.skip_full_width:
+        t0l = layers[0]
+        Zbuf = torch.empty((S, F), dtype=torch.float32, device="cuda")
+        G.griffin_prefill_select(t0l["L"], t0l["X"], cu, k, t0l["idx"], Z_out=Zbuf, workspace=ws_pre, stream=stream)
+        W2p = t0l["W2"].t().contiguous()        # the paper's W_2 layout [d][D_ff] (plumbing, untimed)
+        Yp = torch.empty((S, d), dtype=tdt, device="cuda")
+        ws_po = torch.empty(max(G.griffin_prompt_out_workspace_bytes(S, F, d), 256), dtype=torch.uint8, device="cuda")
+        pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        for rep in range(6):
+            if rep == 1:
+                pe[0].record()
+            G.griffin_ff_prompt_out(Zbuf, W2p, Yp, workspace=ws_po, stream=stream)
+        pe[1].record()
+        torch.cuda.synchronize()
+        prompt_out_us = pe[0].elapsed_time(pe[1]) * 1e3 / 5
+        del Zbuf, W2p, Yp
+
     ms_per_step = wall * 1e3 / args.steps
     sel_ms = sum(e[0].elapsed_time(e[1]) for e in stage_ev) / len(stage_ev)
     dec_ms = sum(e[1].elapsed_time(e[2]) for e in stage_ev) / len(stage_ev)
@@ -284,6 +303,8 @@ def main():
             "pruned_over_full_latency": (u / full_us) if full_us else None,
         },
         "select_us_per_layer": sel_ms * 1e3 / n_layers,
+        "prompt_out": None if prompt_out_us is None else {
+            "us_per_layer": prompt_out_us, "TFLOPs": 2.0 * S * F * d / (prompt_out_us * 1e-6) / 1e12},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, k, *host_w0)

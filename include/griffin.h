@@ -155,6 +155,24 @@ int griffin_ff_decode_indexed(const griffin_layer *L, const int32_t *idx, int32_
                               size_t workspace_bytes, void *stream);
 
 /*
+ * The prompt's own output (Section 5.1: the prompt phase uses the full FF block; Eq. 1):
+ *   Y = Z W_2^T + b_2  for the activations Z written by griffin_prefill_select (Z_out).
+ *   Z    [total_tokens][d_ff] fp32, row stride ldz elements
+ *   W2p  the paper's W_2, [d][d_ff] (row c = output feature c), row stride ldw elements, in
+ *        `dtype`; this is the transpose of the neuron-major W2 of griffin_layer
+ *   b2   [d] in `dtype`, or NULL
+ *   Y    [total_tokens][d] in `dtype`, row stride ldy elements
+ *   workspace  griffin_prompt_out_workspace_bytes(total_tokens, d_ff, d) bytes, 16-byte aligned
+ *        (fp32 partial sums when the long contraction over d_ff is cut into ranges; may be 0)
+ * bf16 blocks with d_ff a multiple of 8 and d a multiple of 4 run on the matrix cores (Z is
+ * rounded to bf16 on the way); other shapes take a plain fp32 path (total_tokens <= 2^18).
+ */
+size_t griffin_prompt_out_workspace_bytes(int64_t total_tokens, int32_t d_ff, int32_t d);
+int griffin_ff_prompt_out(const float *Z, int64_t ldz, int64_t total_tokens, int32_t d_ff, int32_t d,
+                          int32_t dtype, const void *W2p, int64_t ldw, const void *b2, void *Y,
+                          int64_t ldy, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Instrumentation for measurement (the generation phase is where the time goes, Section 5.2):
  * the next griffin_ff_decode* call made by this thread records, on that call's stream,
  * event_begin just before its weight-streaming kernel, event_mid between that kernel and the

@@ -68,6 +68,8 @@ _SIGS = {
     "griffin_compact": (ctypes.c_int, [_LP, _vp, _i32, _LP, _vp]),
     "griffin_decode_workspace_bytes": (_sz, [_i32, _i32, _i32]),
     "griffin_trace_next_decode": (ctypes.c_int, [_vp, _vp, _vp]),
+    "griffin_prompt_out_workspace_bytes": (_sz, [_i64, _i32, _i32]),
+    "griffin_ff_prompt_out": (ctypes.c_int, [_vp, _i64, _i64, _i32, _i32, _i32, _vp, _i64, _vp, _vp, _i64, _vp, _sz, _vp]),
     "griffin_ff_decode": (ctypes.c_int, [_LP, _vp, _vp, _i32, _vp, _sz, _vp]),
     "griffin_ff_decode_multi": (ctypes.c_int, [_LP, _i32, _vp, _vp, _vp, _sz, _vp]),
     "griffin_ff_decode_indexed": (ctypes.c_int, [_LP, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
@@ -205,3 +207,17 @@ def griffin_trace_next_decode(event_begin: Optional[int], event_mid: Optional[in
                               event_end: Optional[int]) -> None:
     """Arm one-shot hipEvent_t handles before / between / after the next decode call's two kernels."""
     _check(lib.griffin_trace_next_decode(event_begin, event_mid, event_end), "griffin_trace_next_decode")
+
+
+def griffin_prompt_out_workspace_bytes(total_tokens: int, d_ff: int, d: int) -> int:
+    return int(lib.griffin_prompt_out_workspace_bytes(total_tokens, d_ff, d))
+
+
+def griffin_ff_prompt_out(Z, W2p, Y, *, b2=None, dtype: Optional[int] = None, workspace=None, stream=None) -> None:
+    """Y = Z W2p^T + b2 for the prompt rows (W2p is the paper's W_2, [d][d_ff])."""
+    import torch
+    if dtype is None:
+        dtype = BF16 if W2p.dtype == torch.bfloat16 else F32
+    _check(lib.griffin_ff_prompt_out(_ptr(Z), Z.stride(0), Z.shape[0], Z.shape[1], W2p.shape[0], dtype,
+                                     _ptr(W2p), W2p.stride(0), _ptr(b2), _ptr(Y), Y.stride(0),
+                                     _ptr(workspace), _nbytes(workspace), _stream(stream)), "griffin_ff_prompt_out")

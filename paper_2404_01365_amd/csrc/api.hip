@@ -218,6 +218,31 @@ int griffin_compact(const griffin_layer *L, const int32_t *idx, int32_t k, const
     return launch_compact(*L, idx, k, *C, (hipStream_t)stream);
 }
 
+size_t griffin_prompt_out_workspace_bytes(int64_t total_tokens, int32_t d_ff, int32_t d)
+{
+    if (total_tokens < 1 || d_ff < 1 || d < 1 || total_tokens > ((int64_t)1 << 30))
+        return 0;
+    return ff2_workspace_bytes(total_tokens, d_ff, d);
+}
+
+int griffin_ff_prompt_out(const float *Z, int64_t ldz, int64_t total_tokens, int32_t d_ff, int32_t d,
+                          int32_t dtype, const void *W2p, int64_t ldw, const void *b2, void *Y, int64_t ldy,
+                          void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!Z || !W2p || !Y || total_tokens < 0)
+        return GRIFFIN_EINVAL;
+    if (dtype != GRIFFIN_F32 && dtype != GRIFFIN_BF16)
+        return GRIFFIN_EINVAL;
+    if (d_ff < 1 || d < 1 || d_ff > MAX_DIM || d > MAX_DIM || ldz < d_ff || ldw < d_ff || ldy < d)
+        return GRIFFIN_ESHAPE;
+    const bool tiles = dtype == GRIFFIN_BF16 && d_ff % 8 == 0 && d % 4 == 0 && ldz % 4 == 0 && ldw % 8 == 0 &&
+                       aligned16(Z) && aligned16(W2p);
+    if (total_tokens > ((int64_t)1 << 30) || (!tiles && total_tokens > ((int64_t)1 << 18)))
+        return GRIFFIN_EUNSUPPORTED;
+    return launch_ff2(Z, ldz, total_tokens, d_ff, d, dtype == GRIFFIN_BF16, W2p, ldw, b2, Y, ldy,
+                      (float *)workspace, workspace_bytes, (hipStream_t)stream);
+}
+
 int griffin_trace_next_decode(void *event_begin, void *event_mid, void *event_end)
 {
     set_decode_probe((hipEvent_t)event_begin, (hipEvent_t)event_mid, (hipEvent_t)event_end);

@@ -122,6 +122,10 @@ int launch_stat_shared(const float *s, const SeqTable &seqs, int32_t n, float *s
 int launch_compact(const griffin_layer &L, const int32_t *idx, int32_t k, const griffin_layer &C,
                    hipStream_t st);
 
+int launch_ff2(const float *Z, int64_t ldz, int64_t M, int32_t F, int32_t d, bool bf16, const void *W2p,
+               int64_t ldw, const void *b2, void *Y, int64_t ldy, float *ws, size_t ws_bytes, hipStream_t st);
+size_t ff2_workspace_bytes(int64_t M, int32_t F, int32_t d);
+
 struct DecodeJob {
     int32_t d, n, act, batch;
     bool bf16;

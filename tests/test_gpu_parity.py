@@ -302,3 +302,30 @@ def test_shared_set_for_a_batch_end_to_end():
     cw = [oracle.compact(w, idx_ref) for w in (c["Wg"], W1, c["W2"])]
     for b in range(B):
         assert max_rel(got[b], oracle.ff_decode(c["xt"][b], *cw, act)) <= TOL_OUT[dtype]
+
+
+# ------------------------------------------------------------------ the prompt's own output (full block)
+@pytest.mark.parametrize("dtype,d,F,S,bias", [
+    (synth.DT_BF16, 512, 1000, 300, True),     # MFMA tiles, ragged in every dimension
+    (synth.DT_BF16, 256, 4096, 40, True),      # long contraction cut into ranges
+    (synth.DT_BF16, 136, 264, 70, False),      # k tail (264 = 4 * 64 + 8)
+    (synth.DT_BF16, 64, 131, 9, True),         # D_ff not a multiple of 8: plain path
+    (synth.DT_F32, 256, 688, 64, True),        # config-0 shape, fp32
+])
+def test_prompt_output_uses_the_full_block(dtype, d, F, S, bias):
+    act = synth.ACT_SILU
+    c = synth.small_case(d + F + S, d, F, S, dtype, with_bias=bias)
+    L, _ = dev_layer(c["Wg"], c["W1"], c["W2"], act, dtype, c.get("bg"), c.get("b1"), c.get("b2"))
+    idx, s, Z = run_prefill(L, to_dev(c["X"], dtype), [0, S], min(8, F))
+    Zd = torch.from_numpy(Z.astype(np.float32)).cuda()
+    W2p = to_dev(np.ascontiguousarray(c["W2"].T), dtype)          # the paper's W_2: [d][D_ff]
+    Y = torch.empty((S, d), dtype=W2p.dtype, device="cuda")
+    G.griffin_ff_prompt_out(Zd, W2p, Y, b2=to_dev(c.get("b2"), dtype),
+                            workspace=workspace(G.griffin_prompt_out_workspace_bytes(S, F, d)))
+    sync()
+    Z_ref = oracle.ff1(c["X"], c["Wg"], c["W1"], act, c.get("bg"), c.get("b1"))
+    Y_ref = oracle.ff2(Z_ref, c["W2"], c.get("b2"))
+    assert max_rel(to_host(Y), Y_ref) <= TOL_OUT[dtype]
+    # row by row it is the full-width decode of the same token (Eq. 1)
+    y0 = oracle.ff_decode(c["X"][0], c["Wg"], c["W1"], c["W2"], act, c.get("bg"), c.get("b1"), c.get("b2"))
+    assert max_rel(Y_ref[0], y0) <= 1e-12
