@@ -25,6 +25,8 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;   // one 16-byte chu
 constexpr int G_BN = 128, G_BK = 64;
 constexpr int G_THREADS = 256;
 constexpr int F_BM = 64, F_BN = 64, F_BK = 16;
+// s_waitcnt immediate that waits for vmcnt <= n only (expcnt / lgkmcnt fields left at "no wait")
+constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 
 struct Ff1Params {
     const void *X, *Wg, *W1, *bg, *b1;
@@ -86,33 +88,135 @@ __device__ __forceinline__ void ff1_mfma_epilogue(const Ff1Params &p, f32x16 (&a
 }
 
 // ------------------------------------------------------------------------------------ bf16 / MFMA, direct-to-LDS
-// Main path (d a multiple of 32).  Operand tiles go from global memory straight into LDS
-// (global_load_lds_dwordx4: lane l of a wave instruction fills 16-byte slot l of a 1 KB region,
-// no VGPR staging, no ds_write), BK = 32, four LDS stages, so three k-tiles (~3000 MFMA
-// cycles) of loads are in flight.  A row of a stage is 64 B = 4 slots; logical chunk c of row r
-// sits in slot c ^ ((r >> 2) & 3), which keeps the ds_read_b128 operand fetches conflict-free;
-// the swizzle is applied by choosing which global chunk each lane loads.  The loop body is
-// branch-free (loads past the last k-tile re-read the last one into a dead stage) so that the
-// scheduler can interleave LDS reads and loads between MFMAs: k-step 1's fragments are read
-// under k-step 0's MFMAs, the next tile's first fragments and the tile three ahead under k-step
-// 1's.  One bare s_barrier per k-tile, preceded by the vmcnt wait that says tile kt+1 landed.
+// Epilogue of the main kernel.  Its MFMAs take the weight fragment as the first operand, so the
+// accumulator tiles are transposed: a lane holds ONE token (column l31 of the 32x32 tile) and the
+// neurons (i>>2)*8 + lh*4 + (i&3): four consecutive neurons per group of four registers.  Z is
+// then written 16 bytes at a time and a token's sum of squares needs no cross-lane step (the
+// four partials per token, one per (wn, lh), meet in LDS).
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+template <int ACT, bool GATED, int MI>
+__device__ __forceinline__ void ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (&accU)[MI][2], f32x16 (&accG)[MI][2],
+                                                    float (*rs)[64 * MI], uint32_t stage_lds, int m0, int n0, int tile_n)
+{
+    constexpr int BM = 64 * MI;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1, l31 = lane & 31, lh = lane >> 5;
+    const bool vec = ((p.F | (int32_t)p.ldz) & 3) == 0 && ((uintptr_t)p.Z & 15) == 0;
+    const bool hb = p.b1 != nullptr || (GATED && p.bg != nullptr);
+    const uint16_t *b1p = (const uint16_t *)p.b1, *bgp = (const uint16_t *)p.bg;
+    if (vec && !hb) {
+        // The usual case (no biases, 16-byte aligned rows of Z, F a multiple of 4).  A wave's
+        // 32-token x 64-neuron block goes through a private LDS patch (rows padded to 272 B, the
+        // stages are dead by now) and leaves as 16-byte stores that cover four whole 256-byte
+        // row pieces per instruction; storing straight from the accumulator layout would touch
+        // 32 different rows with 32 bytes each.
+        constexpr int PR = 272;                                  // padded row, bytes
+        const uint32_t patch = stage_lds + (uint32_t)(wave * 32 * PR);
+        const uint32_t wr = patch + (uint32_t)(l31 * PR + lh * 16);
+        const int rrow = lane >> 4, rch = lane & 15;
+        const uint32_t rd = patch + (uint32_t)(rrow * PR + rch * 16);
+        const int ncol = n0 + wn * 64 + rch * 4;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int lrow = wm * (32 * MI) + mi * 32 + l31;
+            float sq = 0.0f;
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    f32x4_t v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float u = accU[mi][ni][g * 4 + e];
+                        v[e] = GATED ? act_apply_t<ACT>(accG[mi][ni][g * 4 + e]) * u : act_apply_t<ACT>(u);
+                    }
+                    if (n0 + wn * 64 + ni * 32 + g * 8 + lh * 4 >= p.F)
+                        v = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
+                    sq = fmaf(v[0], v[0], sq); sq = fmaf(v[1], v[1], sq);
+                    sq = fmaf(v[2], v[2], sq); sq = fmaf(v[3], v[3], sq);
+                    asm volatile("ds_write_b128 %0, %1" :: "v"(wr + (uint32_t)((ni * 32 + g * 8) * 4)), "v"(v) : "memory");
+                }
+            }
+            rs[wn * 2 + lh][lrow] = sq;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            // rows 4j + rrow of the patch, 16 bytes per lane
+            const int tok0 = m0 + wm * (32 * MI) + mi * 32 + rrow;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                f32x4_t v;
+                asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(rd + (uint32_t)(j * 4 * PR)) : "memory");
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v) :: "memory");
+                const int tok = tok0 + 4 * j;
+                if (tok < p.M && ncol < p.F)
+                    *(f32x4_t *)(p.Z + (int64_t)tok * p.ldz + ncol) = v;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int lrow = wm * (32 * MI) + mi * 32 + l31;
+            const bool rowok = m0 + lrow < p.M;
+            float *zrow = p.Z + (int64_t)min(m0 + lrow, p.M - 1) * p.ldz;
+            float sq = 0.0f;
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int col = n0 + wn * 64 + ni * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
+                    const int cj = min(col, p.F - 1);
+                    float u = accU[mi][ni][i];
+                    float gt = GATED ? accG[mi][ni][i] : 0.0f;
+                    if (b1p) u += bf16_bits_to_f32(b1p[cj]);
+                    if (GATED && bgp) gt += bf16_bits_to_f32(bgp[cj]);
+                    const float z = GATED ? act_apply_t<ACT>(gt) * u : act_apply_t<ACT>(u);
+                    if (col < p.F) {
+                        sq = fmaf(z, z, sq);
+                        if (rowok)
+                            zrow[col] = z;
+                    }
+                }
+            }
+            rs[wn * 2 + lh][lrow] = sq;
+        }
+    }
+    __syncthreads();
+    for (int r = tid; r < BM; r += G_THREADS)
+        if (m0 + r < p.M)
+            p.rowpart[(int64_t)(m0 + r) * p.nt + tile_n] = (rs[0][r] + rs[1][r]) + (rs[2][r] + rs[3][r]);
+}
+
+// Main path (d a multiple of 64).  Operand tiles go from global memory straight into LDS
+// (buffer_load_dwordx4 ... lds: lane l of a wave instruction fills 16-byte slot l of a 1 KB
+// region; no VGPR staging, no ds_write).  A k-tile is BK = 64 elements = one whole 128-byte
+// cache line per row: with half lines the other half is evicted from the 32 KB vector L1
+// before the next k-tile asks for it, every line crosses the L2->L1 path twice and that path
+// (64 B/clk) becomes the bound.  An instruction covers 8 rows x 128 B.  Two LDS stages; a row
+// of a stage is 8 slots, logical chunk c of row r in slot c ^ (r & 7), which keeps the
+// ds_read_b128 operand fetches conflict-free; the swizzle is applied by choosing which global
+// chunk each lane loads.  Per k-tile: four k-steps of MFMAs on fragments read one k-step ahead;
+// after the third, vmcnt(0) + one bare s_barrier say that the next tile has landed for every
+// wave and that every wave has read its last fragment of this tile, so the loads of the tile
+// after next go into this tile's stage under the fourth k-step (first half) and under the next
+// tile's first k-step (second half).  Loads past the last k-tile re-read the last one into a
+// dead stage, which keeps the loop body branch-free.
 typedef __attribute__((address_space(3))) void lds_void_t;
-typedef __attribute__((address_space(1))) const void gbl_cvoid_t;
 
 template <int ACT, bool GATED, int MI>
 __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
 {
-    constexpr int BM = 64 * MI;
-    constexpr int NS = 4, BK = 32;
-    constexpr int A_SLOTS = BM * 4, B_SLOTS = G_BN * 4;
-    constexpr int STAGE = A_SLOTS + (GATED ? 2 : 1) * B_SLOTS;
-    constexpr int AQ = MI;                       // 16-row regions of X per wave per k-tile
-    constexpr int NLOADS = AQ + (GATED ? 4 : 2);  // LDS-DMA instructions per wave per k-tile
-    // s_waitcnt immediates: vmcnt in bits [3:0] and [15:14], expcnt/lgkmcnt fields left at "no wait"
-    constexpr int WAIT_ONE_TILE = 0x0F70 | (NLOADS & 15) | ((NLOADS >> 4) << 14);
-    constexpr int WAIT_TWO_TILES = 0x0F70 | ((2 * NLOADS) & 15) | (((2 * NLOADS) >> 4) << 14);
-    __shared__ u32x4 lds[NS * STAGE];
-    __shared__ float rs[2][BM];
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass has no buffer-descriptor builtins; it only needs the launch stub
+#ifdef FF1_TIMING
+    const uint64_t tk0 = __builtin_readcyclecounter(), wk0 = wall_clock64();
+#endif
+    constexpr int BM = 64 * MI, BK = 64;
+    constexpr int STAGE = (BM + (GATED ? 2 : 1) * G_BN) * 8;   // 16-byte slots per stage
+    constexpr int W1_SLOT = BM * 8, WG_SLOT = (BM + G_BN) * 8;
+    constexpr int XQ = BM / 32, WQ = G_BN / 32;                // 8-row regions per wave per k-tile
+    constexpr int NLOADS = XQ + (GATED ? 2 : 1) * WQ;          // LDS-DMA instructions per wave per k-tile
+    constexpr int H1 = NLOADS / 2;
+    __shared__ u32x4 lds[2 * STAGE];
+    __shared__ float rs[4][BM];
 
     // XCD-aware tile order
     const int nblk = p.mt * p.nt;
@@ -127,37 +231,41 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
 
-    // loader: lane -> (row of the region, slot in the row) -> global chunk (un-swizzled)
-    const int lrow = lane >> 2, lp = lane & 3;
-    int64_t xoff[AQ], woff[2];
+    // loader: lane -> (row of the 8-row region, slot in the row) -> global chunk (un-swizzled).
+    // Byte offsets are relative to the tile's first row and fit 32 bits (checked at launch).
+    const int lrow = lane >> 3, lchunk = (lane & 7) ^ lrow;
+    uint32_t xvo[XQ], wvo[WQ];
 #pragma unroll
-    for (int q = 0; q < AQ; ++q) {
-        const int row = (wave * AQ + q) * 16 + lrow;
-        xoff[q] = (int64_t)min(m0 + row, p.M - 1) * p.ldx + (lp ^ ((row >> 2) & 3)) * 8;
-    }
+    for (int q = 0; q < XQ; ++q)
+        xvo[q] = (uint32_t)min((wave * XQ + q) * 8 + lrow, p.M - 1 - m0) * (uint32_t)(p.ldx * 2) + lchunk * 16;
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int row = (wave * 2 + q) * 16 + lrow;
-        woff[q] = (int64_t)min(n0 + row, p.F - 1) * p.ldw + (lp ^ ((row >> 2) & 3)) * 8;
-    }
-    const uint16_t *Xp = (const uint16_t *)p.X, *W1p = (const uint16_t *)p.W1, *Wgp = (const uint16_t *)p.Wg;
+    for (int q = 0; q < WQ; ++q)
+        wvo[q] = (uint32_t)min((wave * WQ + q) * 8 + lrow, p.F - 1 - n0) * (uint32_t)(p.ldw * 2) + lchunk * 16;
+    // raw buffer descriptors (32-bit data format word of gfx9-family raw buffers); every access is
+    // in range by construction, the record count is not relied upon
+    constexpr int RSRC_FLAGS = 0x00020000, RSRC_RECORDS = 0x7FFFFFFE;
+    const __amdgpu_buffer_rsrc_t rX = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)((const uint16_t *)p.X + (int64_t)m0 * p.ldx), 0, RSRC_RECORDS, RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t rW1 = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)((const uint16_t *)p.W1 + (int64_t)n0 * p.ldw), 0, RSRC_RECORDS, RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t rWg = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)((const uint16_t *)(GATED ? p.Wg : p.W1) + (int64_t)n0 * p.ldw), 0, RSRC_RECORDS, RSRC_FLAGS);
     const int KT = p.d / BK;
 
-#define FF1_ISSUE(kt_)                                                                                   \
+// LDS-DMA instruction number q (0 .. NLOADS-1: the X regions, then W1, then Wg) of k-tile kt_
+#define FF1_LOAD_ONE(kt_, q)                                                                             \
     {                                                                                                    \
-        u32x4 *st_ = lds + ((kt_) % NS) * STAGE;                                                         \
-        const int k0_ = min((kt_), KT - 1) * BK;                                                         \
-        _Pragma("unroll") for (int q = 0; q < AQ; ++q)                                                   \
-            __builtin_amdgcn_global_load_lds((gbl_cvoid_t *)(Xp + xoff[q] + k0_),                        \
-                                             (lds_void_t *)(st_ + (wave * AQ + q) * 64), 16, 0, 0);      \
-        _Pragma("unroll") for (int q = 0; q < 2; ++q)                                                    \
-            __builtin_amdgcn_global_load_lds((gbl_cvoid_t *)(W1p + woff[q] + k0_),                       \
-                                             (lds_void_t *)(st_ + A_SLOTS + (wave * 2 + q) * 64), 16, 0, 0); \
-        if (GATED) {                                                                                     \
-            _Pragma("unroll") for (int q = 0; q < 2; ++q)                                                \
-                __builtin_amdgcn_global_load_lds((gbl_cvoid_t *)(Wgp + woff[q] + k0_),                   \
-                                                 (lds_void_t *)(st_ + A_SLOTS + B_SLOTS + (wave * 2 + q) * 64), 16, 0, 0); \
-        }                                                                                                \
+        u32x4 *st_ = lds + ((kt_) & 1) * STAGE;                                                          \
+        const int so_ = min((kt_), KT - 1) * (BK * 2);                                                   \
+        if ((q) < XQ)                                                                                    \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rX, (lds_void_t *)(st_ + (wave * XQ + (q) % XQ) * 64), 16, \
+                                                     xvo[(q) % XQ], so_, 0, 0);                          \
+        else if ((q) < XQ + WQ)                                                                          \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rW1, (lds_void_t *)(st_ + W1_SLOT + (wave * WQ + ((q) - XQ) % WQ) * 64), 16, \
+                                                     wvo[((q) - XQ) % WQ], so_, 0, 0);                   \
+        else if (GATED)                                                                                  \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rWg, (lds_void_t *)(st_ + WG_SLOT + (wave * WQ + ((q) - XQ) % WQ) * 64), 16, \
+                                                     wvo[((q) - XQ) % WQ], so_, 0, 0);                   \
     }
 // Operand fragments are fetched with ds_read_b128 written as inline asm: the compiler makes every
 // LDS load it knows about wait for ALL LDS-DMA in flight (it cannot tell the stages apart), which
@@ -184,37 +292,39 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
                 accG[mi][ni][i] = 0.0f;
             }
 
-    const int l31 = lane & 31, lh = lane >> 5, sw = (l31 >> 2) & 3;
+    const int l31 = lane & 31, lh = lane >> 5, sw = l31 & 7;
     // byte addresses (inside a stage) of this lane's fragment rows, per k-step
-    uint32_t abase[2], bbase[2];
+    uint32_t abase[4], bbase[4];
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
+    for (int kk = 0; kk < 4; ++kk) {
         const int ch = (2 * kk + lh) ^ sw;
-        abase[kk] = (uint32_t)(((wm * (32 * MI) + l31) * 4 + ch) * 16);
-        bbase[kk] = (uint32_t)((A_SLOTS + (wn * 64 + l31) * 4 + ch) * 16);
+        abase[kk] = (uint32_t)(((wm * (32 * MI) + l31) * 8 + ch) * 16);
+        bbase[kk] = (uint32_t)(((BM + wn * 64 + l31) * 8 + ch) * 16);
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void_t *)lds;   // LDS byte address of stage 0
     u32x4 fa[2][MI], f1[2][2], fg[2][2];
     constexpr int NREADS = MI + (GATED ? 4 : 2);
     constexpr int NMFMA = MI * 2;                  // MFMA pairs (up, gate) or singles per k-step
-    constexpr int NSLOTS = NMFMA > NREADS ? NMFMA : NREADS;   // interleaving slots per k-step (NLOADS == NREADS)
+    constexpr int NSLOTS = NMFMA > NREADS ? NMFMA : NREADS;   // interleaving slots per k-step
+    static_assert(H1 <= NSLOTS && NLOADS - H1 <= NSLOTS, "the loads of a k-tile must fit two k-steps");
 
-// read number r (0 .. NREADS-1) of fragment set F_ from stage address sa_/sb_
+// read number r (0 .. NREADS-1) of fragment set F_ from stage addresses sa_/sb_ (32 rows = 4096 B apart)
 #define FF1_READ_ONE(F_, r, sa_, sb_)                                                          \
     {                                                                                          \
-        if ((r) < MI) FF1_DS_READ(fa[F_][(r) % MI], sa_, ((r) % MI) * 2048);                   \
-        else if ((r) < MI + 2) FF1_DS_READ(f1[F_][((r) - MI) % 2], sb_, (((r) - MI) % 2) * 2048); \
-        else FF1_DS_READ(fg[F_][((r) - MI) % 2], sb_, B_SLOTS * 16 + (((r) - MI) % 2) * 2048); \
+        if ((r) < MI) FF1_DS_READ(fa[F_][(r) % MI], sa_, ((r) % MI) * 4096);                   \
+        else if ((r) < MI + 2) FF1_DS_READ(f1[F_][((r) - MI) % 2], sb_, (((r) - MI) % 2) * 4096); \
+        else FF1_DS_READ(fg[F_][((r) - MI) % 2], sb_, G_BN * 128 + (((r) - MI) % 2) * 4096);   \
     }
-// MFMA(s) number m (0 .. NMFMA-1) of fragment set F_: tile (mi, ni) of the up product and, gated, of the gate product
+// MFMA(s) number m (0 .. NMFMA-1) of fragment set F_: tile (mi, ni) of the up product and, gated,
+// of the gate product; weights first, so the result tile is neurons x tokens
 #define FF1_MFMA_ONE(F_, m)                                                                    \
     {                                                                                          \
         const int mi_ = (m) / 2, ni_ = (m) % 2;                                                \
         accU[mi_][ni_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                              \
-            __builtin_bit_cast(bf16x8, fa[F_][mi_]), __builtin_bit_cast(bf16x8, f1[F_][ni_]), accU[mi_][ni_], 0, 0, 0); \
+            __builtin_bit_cast(bf16x8, f1[F_][ni_]), __builtin_bit_cast(bf16x8, fa[F_][mi_]), accU[mi_][ni_], 0, 0, 0); \
         if (GATED)                                                                             \
             accG[mi_][ni_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                          \
-                __builtin_bit_cast(bf16x8, fa[F_][mi_]), __builtin_bit_cast(bf16x8, fg[F_][ni_]), accG[mi_][ni_], 0, 0, 0); \
+                __builtin_bit_cast(bf16x8, fg[F_][ni_]), __builtin_bit_cast(bf16x8, fa[F_][mi_]), accG[mi_][ni_], 0, 0, 0); \
     }
 #define FF1_WAIT_FRAGS(F_)                                                                     \
     {                                                                                          \
@@ -225,11 +335,31 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
             asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(fa[F_][0]), "+v"(fa[F_][1]),            \
                          "+v"(f1[F_][0]), "+v"(f1[F_][1]), "+v"(fg[F_][0]), "+v"(fg[F_][1]));  \
     }
+// one k-step: MFMAs on fragment set FM_, the reads of set FR_ (k-step KR_ of the stage at sr_)
+// and up to NSLOTS loads (numbers L0_ .. L1_-1 of k-tile LT_) interleaved underneath
+#define FF1_KSTEP(FM_, FR_, sr_, KR_, LT_, L0_, L1_)                                           \
+    {                                                                                          \
+        const uint32_t sa = (sr_) + abase[KR_], sb = (sr_) + bbase[KR_];                       \
+        FF1_PIN();                                                                             \
+        _Pragma("unroll") for (int m = 0; m < NSLOTS; ++m)                                     \
+        {                                                                                      \
+            if (m < NREADS)                                                                    \
+                FF1_READ_ONE(FR_, m, sa, sb)                                                   \
+            if ((L0_) + m < (L1_))                                                             \
+                FF1_LOAD_ONE(LT_, (L0_) + m)                                                   \
+            if (m < NMFMA)                                                                     \
+                FF1_MFMA_ONE(FM_, m)                                                           \
+            FF1_PIN();                                                                         \
+        }                                                                                      \
+    }
 
-    FF1_ISSUE(0)
-    FF1_ISSUE(1)
-    FF1_ISSUE(2)
-    __builtin_amdgcn_s_waitcnt(WAIT_TWO_TILES);      // tile 0 landed
+#pragma unroll
+    for (int q = 0; q < NLOADS; ++q)
+        FF1_LOAD_ONE(0, q)
+#pragma unroll
+    for (int q = 0; q < H1; ++q)
+        FF1_LOAD_ONE(1, q)
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(H1));        // tile 0 landed
     FF1_BARRIER()
     if (!GATED) {
         fg[0][0] = fg[0][1] = fg[1][0] = fg[1][1] = (u32x4){0u, 0u, 0u, 0u};
@@ -240,66 +370,49 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
         for (int r = 0; r < NREADS; ++r)
             FF1_READ_ONE(0, r, sa, sb)
     }
+#ifdef FF1_TIMING
+    const uint64_t tk1 = __builtin_readcyclecounter();
+#endif
     for (int kt = 0; kt < KT; ++kt) {
-        const uint32_t st_cur = lds0 + (uint32_t)((kt % NS) * STAGE * 16);
-        const uint32_t st_nxt = lds0 + (uint32_t)(((kt + 1) % NS) * STAGE * 16);
-        // ---- k-step 0 of tile kt; k-step 1's fragments are fetched underneath
+        const uint32_t st_cur = lds0 + (uint32_t)((kt & 1) * STAGE * 16);
+        const uint32_t st_nxt = lds0 + (uint32_t)(((kt + 1) & 1) * STAGE * 16);
         FF1_WAIT_FRAGS(0)
-        {
-            const uint32_t sa = st_cur + abase[1], sb = st_cur + bbase[1];
-            FF1_PIN();
-#pragma unroll
-            for (int m = 0; m < NSLOTS; ++m) {
-                if (m < NREADS)
-                    FF1_READ_ONE(1, m, sa, sb)
-                if (m < NMFMA)
-                    FF1_MFMA_ONE(0, m)
-                FF1_PIN();
-            }
-        }
-        // tile kt+1 has landed for this wave when only tile kt+2's loads are outstanding; past the
-        // barrier it has landed for every wave, and every wave is done reading tile kt-1, whose
-        // stage the loads of tile kt+3 overwrite
+        FF1_KSTEP(0, 1, st_cur, 1, kt + 1, H1, NLOADS)     // second half of the next tile's loads
         FF1_WAIT_FRAGS(1)
-        __builtin_amdgcn_s_waitcnt(WAIT_ONE_TILE);
-        FF1_BARRIER()
-        // ---- k-step 1; the first fragments of tile kt+1 and the loads of tile kt+3 go underneath
-        {
-            const uint32_t sa = st_nxt + abase[0], sb = st_nxt + bbase[0];
-            u32x4 *st_ = lds + ((kt + 3) % NS) * STAGE;
-            const int k0_ = min(kt + 3, KT - 1) * BK;
-            FF1_PIN();
-#pragma unroll
-            for (int m = 0; m < NSLOTS; ++m) {
-                if (m < NREADS)
-                    FF1_READ_ONE(0, m, sa, sb)
-                if (m < AQ)
-                    __builtin_amdgcn_global_load_lds((gbl_cvoid_t *)(Xp + xoff[m % AQ] + k0_),
-                                                     (lds_void_t *)(st_ + (wave * AQ + (m % AQ)) * 64), 16, 0, 0);
-                else if (m < AQ + 2)
-                    __builtin_amdgcn_global_load_lds((gbl_cvoid_t *)(W1p + woff[(m - AQ) % 2] + k0_),
-                                                     (lds_void_t *)(st_ + A_SLOTS + (wave * 2 + (m - AQ) % 2) * 64), 16, 0, 0);
-                else if (GATED && m < AQ + 4)
-                    __builtin_amdgcn_global_load_lds((gbl_cvoid_t *)(Wgp + woff[(m - AQ) % 2] + k0_),
-                                                     (lds_void_t *)(st_ + A_SLOTS + B_SLOTS + (wave * 2 + (m - AQ) % 2) * 64), 16, 0, 0);
-                if (m < NMFMA)
-                    FF1_MFMA_ONE(1, m)
-                FF1_PIN();
-            }
-        }
+        FF1_KSTEP(1, 0, st_cur, 2, 0, 0, 0)
+        FF1_WAIT_FRAGS(0)
+        FF1_KSTEP(0, 1, st_cur, 3, 0, 0, 0)
+        FF1_WAIT_FRAGS(1)
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));          // tile kt+1 has landed (this wave's part)
+        FF1_BARRIER()                                      // ... every wave's part; tile kt is read out
+        FF1_KSTEP(1, 0, st_nxt, 0, kt + 2, 0, H1)          // first half of the loads of the tile after next
     }
     FF1_WAIT_FRAGS(0)                                 // the reads issued for the tile past the end
-    __builtin_amdgcn_s_waitcnt(0x0F70);               // no LDS-DMA may outlive the loop
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));         // no LDS-DMA may outlive the loop
     FF1_BARRIER()
-#undef FF1_ISSUE
+#undef FF1_LOAD_ONE
 #undef FF1_BARRIER
 #undef FF1_DS_READ
 #undef FF1_PIN
 #undef FF1_READ_ONE
 #undef FF1_MFMA_ONE
 #undef FF1_WAIT_FRAGS
+#undef FF1_KSTEP
 
-    ff1_mfma_epilogue<ACT, GATED, MI>(p, accU, accG, rs, m0, n0, tile_n);
+#ifdef FF1_TIMING
+    const uint64_t tk2 = __builtin_readcyclecounter();
+#endif
+    ff1_mfma_epilogue_t<ACT, GATED, MI>(p, accU, accG, rs, lds0, m0, n0, tile_n);
+#ifdef FF1_TIMING
+    __syncthreads();
+    const uint64_t tk3 = __builtin_readcyclecounter(), wk3 = wall_clock64();
+    if ((logical == 0 || logical == nblk - 1) && tid == 0) {
+        float *q = p.Z + (logical == 0 ? 0 : 64);
+        q[0] = (float)(tk1 - tk0); q[1] = (float)(tk2 - tk1); q[2] = (float)(tk3 - tk2); q[3] = (float)(wk3 - wk0);
+        q[4] = (float)KT;
+    }
+#endif
+#endif
 }
 
 // ------------------------------------------------------------------------------------ bf16 / MFMA, register-staged
@@ -545,7 +658,8 @@ static void launch_mfma(const Ff1Params &p, bool gated, hipStream_t st)
 {
     const int nblk = p.mt * p.nt;
     dim3 grid(((nblk + 7) / 8) * 8), block(G_THREADS);
-    const bool ktail = p.d % 32 != 0;
+    // the direct-to-LDS kernel wants whole 64-element k-tiles and 32-bit byte offsets inside a tile
+    const bool ktail = p.d % 64 != 0 || p.ldx > (1 << 21) || p.ldw > (1 << 21);
     if (gated) {
         if (ktail) hipLaunchKernelGGL((ff1_bf16_mfma_staged_kernel<ACT, true, MI, true>), grid, block, 0, st, p);
         else hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, true, MI>), grid, block, 0, st, p);
