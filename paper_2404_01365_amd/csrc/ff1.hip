@@ -5,13 +5,13 @@
 // norms of Section 4.1 are finished elsewhere.
 //
 // bf16: a dense contraction, so it runs on the matrix cores.  One workgroup (4 wavefronts, 2x2)
-// owns a 128-token x 128-neuron tile of BOTH products: the X tile is staged once in LDS and
-// feeds two sets of v_mfma_f32_32x32x16_bf16 accumulators (gate and up), so the epilogue finds
-// g_ij and u_ij in the same lane and applies sigma, the gating product, the store of Z and the
-// row sum-of-squares without another pass.  Global->LDS copies are 16-byte, double-buffered
-// through registers; LDS rows are XOR-swizzled in 16-byte chunks so the ds_read_b128 operand
-// fetches are conflict-free.  Workgroup ids are remapped so that each XCD (ids congruent mod 8
-// land on the same XCD) walks a contiguous range of tiles and reuses W tiles in its own L2.
+// owns a 256-token (128 for short prompts) x 128-neuron tile of BOTH products: the X tile is
+// staged once in LDS and feeds two sets of v_mfma_f32_32x32x16_bf16 accumulators (gate and up),
+// so the epilogue finds g_ij and u_ij in the same lane and applies sigma, the gating product,
+// the store of Z and the row sum-of-squares without another pass.  Workgroup ids are remapped so
+// that each XCD (ids congruent mod 8 land on the same XCD) walks a contiguous range of tiles and
+// reuses W tiles in its own L2.  The main kernel loads tiles straight into LDS; a register-staged
+// variant takes the shapes it cannot (d not a multiple of 64).
 //
 // fp32: a plain LDS-tiled FMA kernel (64x64 tile); exists for exactness tests and small cases.
 #include "common.h"
