@@ -30,6 +30,10 @@ _lib.oracle_topk.argtypes = [_i64, _dp, _i64, _ip]
 _lib.oracle_compact.argtypes = [_i64, _i64, _dp, _i64, _ip, _dp]
 _lib.oracle_ff_decode.argtypes = [_i64, _i64, _dp, _dp, _dp, _dp, _dp, _dp, _dp, ctypes.c_int, _dp, _dp]
 _lib.oracle_ff2.argtypes = [_i64, _i64, _i64, _dp, _dp, _dp, _dp]
+_fp = ctypes.POINTER(ctypes.c_float)
+_lib.oracle_weight_norm_score.argtypes = [_i64, _i64, _dp, _dp, _dp]
+_lib.oracle_select_sampled.argtypes = [_i64, _dp, _fp, _i64, _i64, _ip]
+_lib.oracle_jaccard.argtypes = [_i64, _ip, _i64, _ip, _dp]
 for _f in ("oracle_ff1", "oracle_stat", "oracle_stat_shared", "oracle_topk", "oracle_compact",
            "oracle_ff_decode", "oracle_ff2", "oracle_num_threads"):
     getattr(_lib, _f).restype = ctypes.c_int
@@ -131,6 +135,37 @@ def ff2(Z, W2, b2=None) -> np.ndarray:
     Y = np.empty((S, d), dtype=np.float64)
     _check(_lib.oracle_ff2(S, d, n, _p(Z), _p(W2), _p(b2), _p(Y)), "oracle_ff2")
     return Y
+
+
+def weight_norm_score(Wg, W1) -> np.ndarray:
+    """Static magnitude metric: ||W1_j||_2 * ||Wg_j||_2 per neuron (Section 5.1, Setup)."""
+    W1, Wg = _f64(W1), _opt(Wg)
+    n, d = W1.shape
+    out = np.empty(n, dtype=np.float64)
+    _check(_lib.oracle_weight_norm_score(n, d, _p(Wg), _p(W1), _p(out)), "oracle_weight_norm_score")
+    return out
+
+
+def select_sampled(s, e, k: int, k_top: int) -> np.ndarray:
+    """k_top experts by top-k of s, k - k_top by weighted sampling without replacement (Appendix B);
+    e holds one unit-exponential variate per neuron (float32)."""
+    s = _f64(s)
+    e = np.ascontiguousarray(e, dtype=np.float32)
+    assert e.shape == s.shape
+    idx = np.empty(k, dtype=np.int32)
+    _check(_lib.oracle_select_sampled(s.shape[0], _p(s), e.ctypes.data_as(_fp), k, k_top,
+                                      idx.ctypes.data_as(_ip)), "oracle_select_sampled")
+    return idx
+
+
+def jaccard(a, b) -> float:
+    """|A n B| / |A u B| of two index sets (Section 4.1)."""
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    b = np.ascontiguousarray(b, dtype=np.int32)
+    out = ctypes.c_double(0.0)
+    _check(_lib.oracle_jaccard(a.shape[0], a.ctypes.data_as(_ip), b.shape[0], b.ctypes.data_as(_ip),
+                               ctypes.byref(out)), "oracle_jaccard")
+    return float(out.value)
 
 
 def prefill_select(X, Wg, W1, act: int, k: int, bg=None, b1=None) -> Tuple[np.ndarray, np.ndarray]:

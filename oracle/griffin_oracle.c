@@ -235,6 +235,103 @@ int oracle_ff2(int64_t S, int64_t d, int64_t n, const double *Z, const double *W
     return 0;
 }
 
+/*
+ * Static selector of the paper's magnitude baseline (Section 5.1, "Setup"): one score per
+ * neuron from the weights alone, the l2 norm of the neuron's row of W1, multiplied, for GLU
+ * blocks, by the l2 norm of its row of Wg.  (The paper says "neuron-wise norms" without
+ * naming the norm; l2 is the reading taken.)  Wg may be NULL.
+ */
+int oracle_weight_norm_score(int64_t n, int64_t d, const double *Wg, const double *W1, double *score)
+{
+    for (int64_t j = 0; j < n; ++j) {
+        double a = 0.0, b = 0.0;
+        for (int64_t c = 0; c < d; ++c)
+            a += W1[j * d + c] * W1[j * d + c];
+        if (Wg)
+            for (int64_t c = 0; c < d; ++c)
+                b += Wg[j * d + c] * Wg[j * d + c];
+        score[j] = Wg ? sqrt(a) * sqrt(b) : sqrt(a);
+    }
+    return 0;
+}
+
+typedef struct {
+    float q;
+    int32_t j;
+} oracle_qkey;
+
+static int oracle_cmp_q_desc(const void *pa, const void *pb)
+{
+    const oracle_qkey *a = (const oracle_qkey *)pa, *b = (const oracle_qkey *)pb;
+    if (a->q > b->q) return -1;
+    if (a->q < b->q) return 1;
+    return (a->j > b->j) - (a->j < b->j);
+}
+
+/*
+ * Sampling-based selection (Appendix B): k_top experts by top-k of s, the remaining k - k_top
+ * drawn from the other neurons without replacement with probability proportional to s_j
+ * (k_top = 0 is the pure "sampling" row of Table 5, k_top = k/2 its "top-k + sampling" row,
+ * k_top = k plain top-k).  The paper does not say how the draw is made; the reading taken is
+ * the exponential-clocks form of weighted sampling without replacement: neuron j rings at time
+ * e_j / s_j, with e_j a unit-rate exponential variate supplied by the caller (the method's
+ * random numbers are inputs), and the earliest k - k_top rings win.  The winner of "earliest
+ * ring" is decided on q_j = s_j / e_j, largest first, computed in IEEE single precision (the
+ * precision the device decides in), capped at 1e38; ties go to the lowest index; s_j = 0
+ * never beats a positive weight.  The set is returned ascending.
+ */
+int oracle_select_sampled(int64_t F, const double *s, const float *e, int64_t k, int64_t k_top, int32_t *idx)
+{
+    if (k < 0 || k > F || k_top < 0 || k_top > k)
+        return 1;
+    char *taken = (char *)calloc((size_t)(F > 0 ? F : 1), 1);
+    oracle_qkey *keys = (oracle_qkey *)malloc(sizeof(oracle_qkey) * (size_t)(F > 0 ? F : 1));
+    if (!taken || !keys)
+        return 2;
+    int rc = oracle_topk(F, s, k_top, idx);
+    if (rc) {
+        free(keys);
+        free(taken);
+        return rc;
+    }
+    for (int64_t t = 0; t < k_top; ++t)
+        taken[idx[t]] = 1;
+    int64_t m = 0;
+    for (int64_t j = 0; j < F; ++j) {
+        if (taken[j])
+            continue;
+        float q = (float)s[j] / e[j];
+        if (q > 1.0e38f)
+            q = 1.0e38f;
+        keys[m].q = q;
+        keys[m].j = (int32_t)j;
+        ++m;
+    }
+    qsort(keys, (size_t)m, sizeof(oracle_qkey), oracle_cmp_q_desc);
+    for (int64_t t = k_top; t < k; ++t)
+        idx[t] = keys[t - k_top].j;
+    qsort(idx, (size_t)k, sizeof(int32_t), oracle_cmp_i32);
+    free(keys);
+    free(taken);
+    return 0;
+}
+
+/*
+ * Jaccard similarity of two selected sets (Section 4.1, the inter-sample comparison of top-k
+ * sets): |A n B| / |A u B|, by comparing every pair of members.  Members of a set are distinct.
+ */
+int oracle_jaccard(int64_t ka, const int32_t *a, int64_t kb, const int32_t *b, double *out)
+{
+    int64_t inter = 0;
+    for (int64_t i = 0; i < ka; ++i)
+        for (int64_t j = 0; j < kb; ++j)
+            if (a[i] == b[j])
+                ++inter;
+    const int64_t uni = ka + kb - inter;
+    *out = uni > 0 ? (double)inter / (double)uni : 1.0;
+    return 0;
+}
+
 int oracle_num_threads(void)
 {
     int n = 1;

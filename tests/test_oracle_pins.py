@@ -287,3 +287,76 @@ def test_active_parameter_arithmetic_matches_the_paper():
     ff_params = c.n_layers * 3 * c.d * c.d_ff
     assert ff_params == pytest.approx(8.49e9, rel=2e-3)
     assert 13.0e9 - ff_params * (1 - c.k / c.d_ff) == pytest.approx(8.8e9, rel=1e-2)
+
+
+# ------------------------------------------------------------------ static and sampled selectors, set similarity
+def test_weight_norm_score_known_rows_and_library_norms():
+    W1 = np.array([[3.0, 4.0, 0.0, 0.0], [1.0, 0.0, 0.0, 0.0], [0.0, 0.0, 0.0, 0.0]])
+    Wg = np.array([[0.0, 0.0, 12.0, 5.0], [2.0, 0.0, 0.0, 0.0], [7.0, 1.0, 1.0, 1.0]])
+    np.testing.assert_allclose(oracle.weight_norm_score(Wg, W1), [65.0, 2.0, 0.0], rtol=1e-15)
+    np.testing.assert_allclose(oracle.weight_norm_score(None, W1), [5.0, 1.0, 0.0], rtol=1e-15)
+    A, B = rand((7, 11), 51), rand((7, 11), 52)       # non-square: a transposed operand would fail
+    ref = np.linalg.norm(A, axis=1) * np.linalg.norm(B, axis=1)
+    np.testing.assert_allclose(oracle.weight_norm_score(B, A), ref, rtol=1e-13)
+    A2 = A.copy()
+    A2[3] *= -2.5                                      # scaling one neuron's W1 row scales its score only
+    out = oracle.weight_norm_score(B, A2)
+    np.testing.assert_allclose(out[3], 2.5 * ref[3], rtol=1e-13)
+    np.testing.assert_allclose(np.delete(out, 3), np.delete(ref, 3), rtol=1e-13)
+
+
+def test_select_sampled_hand_example_and_limits():
+    s = np.array([4.0, 1.0, 2.0, 0.5])
+    e = np.array([2.0, 0.25, 4.0, 1.0], dtype=np.float32)      # q = s / e = 2, 4, 0.5, 0.5
+    np.testing.assert_array_equal(oracle.select_sampled(s, e, 2, 0), [0, 1])
+    np.testing.assert_array_equal(oracle.select_sampled(s, e, 3, 0), [0, 1, 2])    # tie 0.5 = 0.5 -> lower index
+    np.testing.assert_array_equal(oracle.select_sampled(s, e, 2, 1), [0, 1])      # top-1 of s is 0, then q
+    np.testing.assert_array_equal(oracle.select_sampled(s, e, 2, 2), [0, 2])      # k_top = k is plain top-k
+    rng = np.random.default_rng(7)
+    s = rng.random(50)
+    e = rng.exponential(size=50).astype(np.float32)
+    for k in (1, 10, 50):
+        np.testing.assert_array_equal(oracle.select_sampled(s, e, k, k), oracle.topk(s, k))
+    # equal weights: the earliest clocks (smallest e) win
+    np.testing.assert_array_equal(oracle.select_sampled(np.ones(50), e, 12, 0), np.sort(np.argsort(e, kind="stable")[:12]))
+    # a zero weight is never drawn while positive weights remain, whatever its clock says
+    s0 = s.copy()
+    s0[[3, 17, 40]] = 0.0
+    e0 = e.copy()
+    e0[[3, 17, 40]] = 1e-30
+    got = oracle.select_sampled(s0, e0, 47, 5)
+    assert not set(got) & {3, 17, 40}
+    # the top-k half is always inside the result
+    assert set(oracle.topk(s, 5)) <= set(oracle.select_sampled(s, e, 20, 5))
+
+
+def test_select_sampled_draws_like_sequential_weighted_sampling_without_replacement():
+    # P({a, b}) of drawing two of four items one after the other with probability proportional to
+    # the weight of what is left, written out; the oracle's draws must follow it.
+    w = np.array([5.0, 3.0, 1.5, 0.5])
+    W = w.sum()
+    pairs = list(itertools.combinations(range(4), 2))
+    p_exact = np.array([w[a] / W * w[b] / (W - w[a]) + w[b] / W * w[a] / (W - w[b]) for a, b in pairs])
+    assert p_exact.sum() == pytest.approx(1.0, abs=1e-12)
+    rng = np.random.default_rng(11)
+    n_draws = 40000
+    E = rng.exponential(size=(n_draws, 4)).astype(np.float32)
+    counts = dict.fromkeys(pairs, 0)
+    for t in range(n_draws):
+        a, b = oracle.select_sampled(w, E[t], 2, 0)
+        counts[(int(a), int(b))] += 1
+    freq = np.array([counts[p] for p in pairs]) / n_draws
+    sigma = np.sqrt(p_exact * (1 - p_exact) / n_draws)
+    assert np.all(np.abs(freq - p_exact) < 4.5 * sigma), (freq, p_exact)
+
+
+def test_jaccard_known_sets_and_python_sets():
+    assert oracle.jaccard([1, 2, 3], [2, 3, 4]) == pytest.approx(0.5)
+    assert oracle.jaccard([5, 9], [5, 9]) == 1.0
+    assert oracle.jaccard([0, 1], [2, 3]) == 0.0
+    rng = np.random.default_rng(3)
+    for _ in range(5):
+        a = np.sort(rng.choice(200, 60, replace=False))
+        b = np.sort(rng.choice(200, 45, replace=False))
+        sa, sb = set(a.tolist()), set(b.tolist())
+        assert oracle.jaccard(a, b) == pytest.approx(len(sa & sb) / len(sa | sb), abs=1e-15)
