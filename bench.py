@@ -256,6 +256,38 @@ def main():
         prompt_out_us = pe[0].elapsed_time(pe[1]) * 1e3 / 5
         del Zbuf, W2p, Yp
 
+    # further rows measured outside the timed region: the static weight-norm selector (Section 5.1
+    # setup) and one shared set decoded for a batch of 16 rows (Section 5.3, Eq. 7)
+    extras = None
+    if not args.skip_full_width:
+        t0l = layers[0]
+        sc = torch.empty((F,), dtype=torch.float32, device="cuda")
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        for rep in range(6):
+            if rep == 1:
+                ev[0].record()
+            G.griffin_weight_norm_score(t0l["L"], sc, stream=stream)
+        ev[1].record()
+        Bsh = 16
+        xb = t0l["xt"][:Bsh].contiguous()
+        yb = torch.empty_like(xb)
+        ws_b = torch.empty(G.griffin_decode_workspace_bytes(d, k, Bsh), dtype=torch.uint8, device="cuda")
+        reps_b = 4 * n_rep
+        for rep in range(2):
+            if rep == 1:
+                ev[2].record()
+            for r in range(reps_b):
+                G.griffin_ff_decode(t0l["C"][r % n_rep], xb, yb, Bsh, workspace=ws_b, stream=stream)
+        ev[3].record()
+        torch.cuda.synchronize()
+        wn_us = ev[0].elapsed_time(ev[1]) * 1e3 / 5
+        b_us = ev[2].elapsed_time(ev[3]) * 1e3 / reps_b
+        extras = {
+            "weight_norm_score": {"us_per_layer": wn_us, "GBps": 2 * F * d * w / (wn_us * 1e-6) / 1e9},
+            "shared_set_decode_batch16": {"us_per_call": b_us, "rows": Bsh,
+                                          "GBps_weights_once": (3 * k * d * w + 2 * Bsh * d * w) / (b_us * 1e-6) / 1e9},
+        }
+
     ms_per_step = wall * 1e3 / args.steps
     sel_ms = sum(e[0].elapsed_time(e[1]) for e in stage_ev) / len(stage_ev)
     dec_ms = sum(e[1].elapsed_time(e[2]) for e in stage_ev) / len(stage_ev)
@@ -317,6 +349,8 @@ def main():
         "prompt_out": None if prompt_out_us is None else {
             "us_per_layer": prompt_out_us, "TFLOPs": 2.0 * S * F * d / (prompt_out_us * 1e-6) / 1e12},
     }
+    if extras:
+        out.update(extras)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, k, *host_w0)
     print(json.dumps(out))

@@ -116,6 +116,38 @@ int griffin_stat_shared(const float *s, const int32_t *cu_seqlens_host, int32_t 
                         int32_t n, float *sbar_out, void *stream);
 
 /*
+ * Static selector of the paper's magnitude baseline (Section 5.1, "Setup"): one score per neuron
+ * from the weights alone, ||W1_j||_2, times ||Wg_j||_2 for GLU blocks (the paper names no norm;
+ * l2 is taken).  score_out [L->n] fp32; feed it to griffin_topk.  The prompt still uses the
+ * full block.
+ */
+int griffin_weight_norm_score(const griffin_layer *L, float *score_out, void *stream);
+
+/*
+ * Sampling-based selection (Appendix B): k_top experts by top-k of s, the other k - k_top drawn
+ * from the remaining neurons without replacement with probability proportional to s_j
+ * (k_top = 0: "sampling"; k_top = k/2: "top-k + sampling"; k_top = k: plain top-k).  The draw is
+ * the exponential-clocks form of weighted sampling without replacement: neuron j rings at
+ * e_j / s_j and the earliest rings win, decided on q_j = s_j / e_j in single precision (capped
+ * at 1e38), largest first, ties to the lower index; a zero weight never beats a positive one.
+ *   s [n] fp32 >= 0 (the statistic of Eq. 6, or s_bar of Eq. 7)
+ *   e [n] fp32 > 0: one unit-rate exponential variate per neuron, drawn by the caller (the
+ *     library draws no random numbers)
+ *   idx_out [k] int32 ascending
+ *   workspace griffin_select_sampled_workspace_bytes(n, k_top) bytes, 256-byte aligned
+ */
+size_t griffin_select_sampled_workspace_bytes(int32_t n, int32_t k_top);
+int griffin_select_sampled(const float *s, const float *e, int32_t n, int32_t k, int32_t k_top,
+                           int32_t *idx_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Jaccard similarity of selected sets (Section 4.1): out[a][b] = |E_a n E_b| / |E_a u E_b| for
+ * every pair of the n_sets ascending index lists idx [n_sets][k] (as written by
+ * griffin_prefill_select).  out [n_sets][n_sets] fp32; n_sets <= GRIFFIN_MAX_SEQS.
+ */
+int griffin_jaccard(const int32_t *idx, int32_t n_sets, int32_t k, float *out, void *stream);
+
+/*
  * Compaction (Section 4.2; Eq. 4-5): C->Wg/W1/W2 row t <- L row idx[t], C->bg/b1 entry t <-
  * L entry idx[t]; b2 is not touched (the caller passes L->b2 as C->b2).  C describes
  * caller-allocated device buffers: C->n == k, C->d == L->d, same dtype and act, C->ld >= d.

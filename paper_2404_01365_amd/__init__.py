@@ -66,6 +66,10 @@ _SIGS = {
     "griffin_topk": (ctypes.c_int, [_vp, _i32, _i32, _i32, _vp, _vp]),
     "griffin_stat_shared": (ctypes.c_int, [_vp, _IP, _i32, _i32, _vp, _vp]),
     "griffin_compact": (ctypes.c_int, [_LP, _vp, _i32, _LP, _vp]),
+    "griffin_weight_norm_score": (ctypes.c_int, [_LP, _vp, _vp]),
+    "griffin_select_sampled_workspace_bytes": (_sz, [_i32, _i32]),
+    "griffin_select_sampled": (ctypes.c_int, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _sz, _vp]),
+    "griffin_jaccard": (ctypes.c_int, [_vp, _i32, _i32, _vp, _vp]),
     "griffin_decode_workspace_bytes": (_sz, [_i32, _i32, _i32]),
     "griffin_trace_next_decode": (ctypes.c_int, [_vp, _vp, _vp]),
     "griffin_prompt_out_workspace_bytes": (_sz, [_i64, _i32, _i32]),
@@ -174,6 +178,26 @@ def griffin_stat_shared(s, cu_seqlens: Sequence[int], sbar_out, *, stream=None) 
     n_seqs = len(cu_seqlens) - 1
     _check(lib.griffin_stat_shared(_ptr(s), _cu_array(cu_seqlens), n_seqs, s.shape[-1], _ptr(sbar_out),
                                    _stream(stream)), "griffin_stat_shared")
+
+
+def griffin_weight_norm_score(L: griffin_layer, score_out, *, stream=None) -> None:
+    _check(lib.griffin_weight_norm_score(ctypes.byref(L), _ptr(score_out), _stream(stream)),
+           "griffin_weight_norm_score")
+
+
+def griffin_select_sampled_workspace_bytes(n: int, k_top: int) -> int:
+    return int(lib.griffin_select_sampled_workspace_bytes(n, k_top))
+
+
+def griffin_select_sampled(s, e, k: int, k_top: int, idx_out, *, workspace, stream=None) -> None:
+    _check(lib.griffin_select_sampled(_ptr(s), _ptr(e), s.shape[-1], k, k_top, _ptr(idx_out),
+                                      _ptr(workspace), _nbytes(workspace), _stream(stream)),
+           "griffin_select_sampled")
+
+
+def griffin_jaccard(idx, out, *, stream=None) -> None:
+    n_sets, k = idx.shape
+    _check(lib.griffin_jaccard(_ptr(idx), n_sets, k, _ptr(out), _stream(stream)), "griffin_jaccard")
 
 
 def griffin_compact(L: griffin_layer, idx, k: int, C: griffin_layer, *, stream=None) -> None:

@@ -201,6 +201,46 @@ int griffin_stat_shared(const float *s, const int32_t *cu_seqlens_host, int32_t 
     return launch_stat_shared(s, seqs, n, sbar_out, (hipStream_t)stream);
 }
 
+int griffin_weight_norm_score(const griffin_layer *L, float *score_out, void *stream)
+{
+    int rc = check_layer(L);
+    if (rc != GRIFFIN_OK)
+        return rc;
+    if (!score_out)
+        return GRIFFIN_EINVAL;
+    return launch_weight_norm(*L, score_out, (hipStream_t)stream);
+}
+
+size_t griffin_select_sampled_workspace_bytes(int32_t n, int32_t k_top)
+{
+    if (n < 1 || k_top < 0 || k_top > n)
+        return 0;
+    return align256((size_t)n * sizeof(float)) + align256((size_t)(k_top > 0 ? k_top : 1) * sizeof(int32_t));
+}
+
+int griffin_select_sampled(const float *s, const float *e, int32_t n, int32_t k, int32_t k_top, int32_t *idx_out,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!s || !e || !idx_out)
+        return GRIFFIN_EINVAL;
+    if (n < 1 || n > MAX_DIM || k < 1 || k > n || k_top < 0 || k_top > k)
+        return GRIFFIN_ESHAPE;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < griffin_select_sampled_workspace_bytes(n, k_top))
+        return GRIFFIN_EWORKSPACE;
+    float *q = (float *)workspace;
+    int32_t *idx_top = (int32_t *)((char *)workspace + align256((size_t)n * sizeof(float)));
+    return launch_select_sampled(s, e, n, k, k_top, idx_out, q, idx_top, (hipStream_t)stream);
+}
+
+int griffin_jaccard(const int32_t *idx, int32_t n_sets, int32_t k, float *out, void *stream)
+{
+    if (!idx || !out)
+        return GRIFFIN_EINVAL;
+    if (n_sets < 1 || n_sets > GRIFFIN_MAX_SEQS || k < 1 || k > MAX_DIM)
+        return GRIFFIN_ESHAPE;
+    return launch_jaccard(idx, n_sets, k, out, (hipStream_t)stream);
+}
+
 int griffin_compact(const griffin_layer *L, const int32_t *idx, int32_t k, const griffin_layer *C, void *stream)
 {
     int rc = check_layer(L);

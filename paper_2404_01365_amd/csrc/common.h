@@ -119,6 +119,10 @@ int launch_stat(const float *Z, int64_t ldz, const float *rowpart, int nt, int64
 int stat_row_chunks(int64_t total_tokens, int32_t n_seqs, int32_t F);
 int launch_topk(const float *scores, int32_t n_rows, int32_t n, int32_t k, int32_t *idx, hipStream_t st);
 int launch_stat_shared(const float *s, const SeqTable &seqs, int32_t n, float *sbar, hipStream_t st);
+int launch_weight_norm(const griffin_layer &L, float *score, hipStream_t st);
+int launch_select_sampled(const float *s, const float *e, int32_t n, int32_t k, int32_t k_top, int32_t *idx_out,
+                          float *q, int32_t *idx_top, hipStream_t st);
+int launch_jaccard(const int32_t *idx, int32_t n_sets, int32_t k, float *out, hipStream_t st);
 int launch_compact(const griffin_layer &L, const int32_t *idx, int32_t k, const griffin_layer &C,
                    hipStream_t st);
 

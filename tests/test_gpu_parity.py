@@ -329,3 +329,59 @@ def test_prompt_output_uses_the_full_block(dtype, d, F, S, bias):
     # row by row it is the full-width decode of the same token (Eq. 1)
     y0 = oracle.ff_decode(c["X"][0], c["Wg"], c["W1"], c["W2"], act, c.get("bg"), c.get("b1"), c.get("b2"))
     assert max_rel(Y_ref[0], y0) <= 1e-12
+
+
+# ------------------------------------------------------------------ static and sampled selectors, set similarity
+@pytest.mark.parametrize("dtype,d,F,gated", [
+    (synth.DT_BF16, 512, 1000, True), (synth.DT_BF16, 8, 5, True), (synth.DT_BF16, 4096, 700, False),
+    (synth.DT_F32, 256, 688, True), (synth.DT_F32, 72, 150, False)])
+def test_weight_norm_score_matches_oracle(dtype, d, F, gated):
+    c = synth.small_case(d * 7 + F, d, F, 4, dtype)
+    Wg = c["Wg"] if gated else None
+    L, _ = dev_layer(Wg, c["W1"], c["W2"], synth.ACT_SILU, dtype)
+    out = torch.empty(F, dtype=torch.float32, device="cuda")
+    G.griffin_weight_norm_score(L, out)
+    sync()
+    ref = oracle.weight_norm_score(Wg, c["W1"])
+    np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=2e-6)
+    # the static expert set: top-k of the score (exact where the oracle's boundary gap is open)
+    k = max(F // 2, 1)
+    if oracle.topk_margin(ref, k) > 1e-4:
+        idx = torch.empty((1, k), dtype=torch.int32, device="cuda")
+        G.griffin_topk(out, k, idx)
+        sync()
+        np.testing.assert_array_equal(idx.cpu().numpy()[0], oracle.topk(ref, k))
+
+
+@pytest.mark.parametrize("n,k", [(11008, 5504), (1000, 1), (257, 256), (64, 64)])
+def test_select_sampled_matches_oracle_bitwise(n, k):
+    rng = np.random.default_rng(n + k)
+    s = (rng.random(n) ** 4).astype(np.float32)            # concentrated like the statistic (Appendix A)
+    s[rng.choice(n, n // 10, replace=False)] = 0.0          # neurons that never fired
+    e = rng.exponential(size=n).astype(np.float32)
+    e = np.maximum(e, np.float32(1e-6))
+    e[: n // 8] = np.float32(0.5)                           # equal clocks: ties in q wherever s ties too
+    s[: n // 16] = np.float32(0.25)
+    sd, ed = torch.from_numpy(s).cuda(), torch.from_numpy(e).cuda()
+    for k_top in sorted({0, k // 2, k}):
+        ws = workspace(G.griffin_select_sampled_workspace_bytes(n, k_top))
+        idx = torch.full((k,), -1, dtype=torch.int32, device="cuda")
+        G.griffin_select_sampled(sd, ed, k, k_top, idx, workspace=ws)
+        sync()
+        np.testing.assert_array_equal(idx.cpu().numpy(), oracle.select_sampled(s, e, k, k_top), err_msg="k_top=%d" % k_top)
+
+
+def test_jaccard_of_selected_sets_matches_oracle():
+    rng = np.random.default_rng(12)
+    n, k, B = 5000, 1200, 5
+    s = rng.random((B, n)).astype(np.float32)
+    s[1] = s[0]                                             # identical sets -> 1
+    idx = torch.empty((B, k), dtype=torch.int32, device="cuda")
+    G.griffin_topk(torch.from_numpy(s).cuda(), k, idx)
+    out = torch.empty((B, B), dtype=torch.float32, device="cuda")
+    G.griffin_jaccard(idx, out)
+    sync()
+    sets = idx.cpu().numpy()
+    ref = np.array([[oracle.jaccard(sets[a], sets[b]) for b in range(B)] for a in range(B)])
+    np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=1e-6)
+    assert out[0, 1].item() == 1.0 and np.allclose(np.diag(out.cpu().numpy()), 1.0)
