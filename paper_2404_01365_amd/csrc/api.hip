@@ -293,7 +293,13 @@ size_t griffin_decode_workspace_bytes(int32_t d, int32_t n, int32_t batch)
 {
     if (d < 1 || n < 1 || batch < 1 || batch > GRIFFIN_MAX_BATCH)
         return 0;
-    return (size_t)decode_parts(n, batch) * batch * d * sizeof(float);
+    size_t floats = (size_t)decode_parts(n, batch) * batch * d;
+    if (batch >= DEC_BATCH_MIN_ROWS && decode_batch_supported(d, n, true)) {
+        const size_t fb = decode_batch_workspace_floats(d, n, batch);
+        if (fb > floats)
+            floats = fb;
+    }
+    return floats * sizeof(float);
 }
 
 static int decode_common(const griffin_layer *L0, const griffin_layer *multi, const int32_t *idx, int32_t k,

@@ -146,6 +146,11 @@ struct DecodeJob {
     size_t part_bytes;
 };
 int launch_decode(const DecodeJob &job, hipStream_t st);
+// rows 5.. of a batch through one shared block: matrix-core path (decode_batch.hip)
+bool decode_batch_supported(int32_t d, int32_t n, bool bf16);
+size_t decode_batch_workspace_floats(int32_t d, int32_t n, int32_t batch);
+int launch_decode_batch_front(const DecodeJob &job, int *NR_out, hipStream_t st);
+constexpr int DEC_BATCH_MIN_ROWS = 5;
 int decode_parts(int32_t n, int32_t batch);
 void set_decode_probe(hipEvent_t begin, hipEvent_t mid, hipEvent_t end);
 

@@ -345,8 +345,12 @@ int launch_decode(const DecodeJob &job, hipStream_t st)
     const int R = decode_team_waves(job.d, job.bf16);
     if (R == 0)
         return GRIFFIN_EUNSUPPORTED;
-    const int P = decode_parts(job.n, job.batch);
-    if (job.part_bytes < (size_t)P * job.batch * job.d * sizeof(float))
+    int P = decode_parts(job.n, job.batch);
+    // five rows and more through one shared block: the matrix-core path
+    const bool batch_path = !job.multi && !job.idx && job.batch >= DEC_BATCH_MIN_ROWS &&
+                            decode_batch_supported(job.d, job.n, job.bf16);
+    if (job.part_bytes < (batch_path ? decode_batch_workspace_floats(job.d, job.n, job.batch)
+                                     : (size_t)P * job.batch * job.d) * sizeof(float))
         return GRIFFIN_EWORKSPACE;
 
     DecodeParams p;
@@ -379,6 +383,20 @@ int launch_decode(const DecodeJob &job, hipStream_t st)
     g_probe_begin = g_probe_mid = g_probe_end = nullptr;
     if (ev_begin && hipEventRecord(ev_begin, st) != hipSuccess)
         return set_hip_error(hipGetLastError(), "hipEventRecord");
+
+    if (batch_path) {
+        int rc = launch_decode_batch_front(job, &P, st);
+        if (rc != GRIFFIN_OK)
+            return rc;
+        if (ev_mid && hipEventRecord(ev_mid, st) != hipSuccess)
+            return set_hip_error(hipGetLastError(), "hipEventRecord");
+        dim3 rgrid((job.d / 4 + 3) / 4, job.batch), rblock(256);
+        hipLaunchKernelGGL((ff_decode_reduce_kernel<true, false>), rgrid, rblock, 0, st, job.part, P, job.d, b2, b2m, job.y);
+        rc = check_launch("ff_decode_reduce_kernel");
+        if (rc == GRIFFIN_OK && ev_end && hipEventRecord(ev_end, st) != hipSuccess)
+            return set_hip_error(hipGetLastError(), "hipEventRecord");
+        return rc;
+    }
 
     // rows through one shared block are taken NB at a time (weights streamed once per NB rows)
     const bool shared_block = !job.multi && !job.idx;

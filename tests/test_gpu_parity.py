@@ -76,6 +76,10 @@ def test_ff_decode_matches_oracle(dtype, d, n, act, gated, bias):
     (synth.DT_BF16, 4096, 96, 2, True),       # 2 rows per pass
     (synth.DT_BF16, 3072, 130, 16, False),
     (synth.DT_F32, 264, 77, 7, True),
+    (synth.DT_BF16, 4096, 1001, 16, True),    # matrix-core path: odd neuron count, biases
+    (synth.DT_BF16, 2048, 777, 9, False),     # matrix-core path: 9 of 16 rows used
+    (synth.DT_BF16, 512, 64, 40, False),      # matrix-core path: three groups of rows (16 + 16 + 8)
+    (synth.DT_BF16, 5120, 200, 16, False),    # 10 slices per row: stays on the four-rows-per-pass path
 ])
 def test_ff_decode_batch_shares_one_block(dtype, d, n, batch, bias):
     c = synth.small_case(5 + batch, d, n, 4, dtype, T=batch, with_bias=bias)
@@ -90,6 +94,25 @@ def test_ff_decode_batch_shares_one_block(dtype, d, n, batch, bias):
         assert max_rel(got[t], run_decode(L, x[t:t + 1].contiguous(), batch=1)[0]) <= (2.0 ** -7 if dtype == synth.DT_BF16 else 1e-6)
     # deterministic: a second run gives the same bits
     assert np.array_equal(got, run_decode(L, x, batch=batch))
+
+
+@pytest.mark.parametrize("gated,interleaved", [(True, True), (False, False), (False, True)])
+def test_ff_decode_batch_matrix_core_path_layouts(gated, interleaved):
+    """16 rows through one block on the matrix-core path: Eq. 2 blocks and the interleaved compact layout."""
+    d, n, batch = 1024, 500, 16
+    c = synth.small_case(91, d, n, 4, synth.DT_BF16, T=batch)
+    Wg = c["Wg"] if gated else None
+    L, t = dev_layer(Wg, c["W1"], c["W2"], synth.ACT_GELU_TANH, synth.DT_BF16)
+    k = 300
+    idx_h = np.sort(np.random.default_rng(4).choice(n, k, replace=False)).astype(np.int32)
+    idx = torch.from_numpy(idx_h).cuda()
+    C, keep = empty_compact(L, k, t, interleaved=interleaved)
+    G.griffin_compact(L, idx, k, C)
+    x = to_dev(c["xt"], synth.DT_BF16)
+    got = run_decode(C, x, batch=batch)
+    for b in range(batch):
+        ref = oracle.ff_decode(c["xt"][b], None if Wg is None else Wg[idx_h], c["W1"][idx_h], c["W2"][idx_h], synth.ACT_GELU_TANH)
+        assert max_rel(got[b], ref) <= TOL_OUT[synth.DT_BF16], b
 
 
 # ------------------------------------------------------------------ compaction
