@@ -39,8 +39,8 @@ constexpr int BT_ROWS = 16;              // rows of x per pass
 constexpr int BT_ZBLOCKS = 64;           // neuron groups per workgroup whose Z fits the LDS table
 constexpr int BT_G = 2;                  // neurons per group (MFMA columns in use)
 constexpr int BT_MAX_WG = 256;           // workgroups of the first kernel
-constexpr int BT_COLS = 256;             // columns per workgroup of the second kernel
-constexpr int BT_WAVES2 = 16;            // waves per workgroup of the second kernel
+constexpr int BT_COLS = 512;             // columns per workgroup of the second kernel
+constexpr int BT_WAVES2 = 8;             // waves per workgroup of the second kernel (64 columns each)
 
 struct BatchParams {
     const void *Wg, *W1, *W2, *bg, *b1;
@@ -56,8 +56,8 @@ struct BatchParams {
 
 constexpr int bt_vmcnt(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 
-template <bool GATED, int NSTG, int G>
-__global__ __launch_bounds__(512) void ff_batch_gu_kernel(BatchParams p)
+template <bool GATED, int NSTG, int G, int MAXT>
+__global__ __launch_bounds__(MAXT) void ff_batch_gu_kernel(BatchParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char bt_smem[];
     constexpr int NMAT = GATED ? 2 : 1;
@@ -277,22 +277,22 @@ __global__ __launch_bounds__(512) void ff_batch_gu_kernel(BatchParams p)
 }
 
 // Y partials on the matrix cores: workgroup (nr, cs) owns neurons [j_lo, j_hi) (bounds on
-// multiples of 8, at most 488 of them) and columns cs*256 .. +255; wave w owns 16 of the columns.
+// multiples of 8, at most 488 of them) and columns cs*512 .. +511; wave w owns 64 of the columns
+// (four 16-column MFMA tiles).
 //   D[16 rows of the batch][16 columns] += A[16][32 neurons] * B[32 neurons][16 columns]
 // A is Z: the workgroup first turns its range of Z into bf16 pairs hi + lo (fp32 accuracy is kept
 // by feeding both) laid out [16][range] in LDS.  B is W2, whose memory order (columns
 // contiguous) is the transpose of what an MFMA operand wants (neurons contiguous per lane):
-// every wave brings its own 32-neuron x 16-column pieces (32 bytes per row) into a private LDS
-// ring with one LDS-DMA instruction per 32 neurons, the four waves that share a 128-byte line
-// meeting in the vector L1, and gathers the operand with 16-bit LDS reads.  No wave waits for
-// another after the first barrier.
+// every wave brings its own 32-neuron x 64-column pieces (whole 128-byte lines, 8 rows per
+// LDS-DMA instruction) into a private LDS ring and gathers the operands with 16-bit LDS reads.
+// No wave waits for another after the first barrier.
 constexpr int BD_ZLD = 520;              // elements per row of the Z tables in LDS
 constexpr int BD_RANGE = 480;            // neurons per workgroup before rounding to multiples of 8
-constexpr int BD_DEPTH = 6;              // ring slots (1 KB each) per wave
+constexpr int BD_DEPTH = 3;              // ring slots (32 rows x 128 B = 4 KB each) per wave
 
 __global__ __launch_bounds__(BT_WAVES2 * 64) void ff_batch_down_kernel(BatchParams p, const float *__restrict__ z)
 {
-    __shared__ u32x4_b ring_s[BT_WAVES2 * BD_DEPTH * 64];           // 96 KB
+    __shared__ u32x4_b ring_s[BT_WAVES2 * BD_DEPTH * 256];          // 96 KB
     __shared__ uint16_t zhi[16 * BD_ZLD], zlo[16 * BD_ZLD];         // 2 x 16.25 KB
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -314,69 +314,79 @@ __global__ __launch_bounds__(BT_WAVES2 * 64) void ff_batch_down_kernel(BatchPara
     __syncthreads();
 
     const int bq = lane & 15, q = lane >> 4;
-    const int c0 = cs * BT_COLS + wave * 16;
-    u32x4_b *ring = ring_s + wave * (BD_DEPTH * 64);
+    const int c0 = cs * BT_COLS + wave * 64;
+    u32x4_b *ring = ring_s + wave * (BD_DEPTH * 256);
     const uint32_t ring_a = (uint32_t)(uintptr_t)(lds_void_b *)ring;
     const uint32_t za = (uint32_t)(uintptr_t)(lds_void_b *)zhi + (uint32_t)((bq * BD_ZLD + q * 8) * 2);
     const uint32_t zb = (uint32_t)(uintptr_t)(lds_void_b *)zlo + (uint32_t)((bq * BD_ZLD + q * 8) * 2);
-    const uint16_t *w2 = (const uint16_t *)p.W2 + c0 + (lane & 1) * 8;
-    const int lrow = lane >> 1;
+    const uint16_t *w2 = (const uint16_t *)p.W2 + c0 + (lane & 7) * 8;
+    const int lrow = lane >> 3;
+// the four LDS-DMA instructions of step s_: rows 8u .. 8u+7 of its 32 neurons, 128 bytes per row
 #define BD_ISSUE(s_)                                                                                         \
+    _Pragma("unroll") for (int u = 0; u < 4; ++u)                                                            \
     {                                                                                                        \
-        const int row_ = min(j_lo + min((s_), S - 1) * 32 + lrow, p.n - 1);                                  \
+        const int row_ = min(j_lo + min((s_), S - 1) * 32 + u * 8 + lrow, p.n - 1);                          \
         __builtin_amdgcn_global_load_lds((gbl_cvoid_b *)(w2 + (int64_t)row_ * p.ld),                         \
-                                         (lds_void_b *)(ring + ((s_) % BD_DEPTH) * 64), 16, 0, 0);           \
+                                         (lds_void_b *)(ring + ((s_) % BD_DEPTH) * 256 + u * 64), 16, 0, 0); \
     }
-    f32x4_b acc = {0.f, 0.f, 0.f, 0.f};
+    f32x4_b acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+        acc[t] = (f32x4_b){0.f, 0.f, 0.f, 0.f};
     if (S > 0) {                 // an empty range (very few neurons) still writes its zero partial
 #pragma unroll
     for (int s = 0; s < BD_DEPTH - 1; ++s)
         BD_ISSUE(s)
     // LDS reads by inline asm: reads the compiler knows about would wait for every LDS-DMA in flight
-    const uint32_t gat = (uint32_t)(q * 8 * 32 + bq * 2);      // row 8q of the slot, column bq
+    const uint32_t gat = (uint32_t)(q * 8 * 128 + bq * 2);     // row 8q of the slot, column bq of tile 0
     for (int s = 0; s < S; ++s) {
         BD_ISSUE(s + BD_DEPTH - 1)
-        __builtin_amdgcn_s_waitcnt(bt_vmcnt(BD_DEPTH - 1));    // piece s has landed
-        const uint32_t slot = ring_a + (uint32_t)((s % BD_DEPTH) * 1024) + gat;
-        // eight 16-bit reads into eight registers (two reads in flight into the halves of one register
-        // do not merge), packed in pairs afterwards
-        uint32_t e0, e1, e2, e3, e4, e5, e6, e7;
+        __builtin_amdgcn_s_waitcnt(bt_vmcnt((BD_DEPTH - 1) * 4));   // the pieces of step s have landed
+        const uint32_t slot = ring_a + (uint32_t)((s % BD_DEPTH) * 4096) + gat;
         u32x4_b ah, al;
-        asm volatile("ds_read_u16 %0, %1" : "=v"(e0) : "v"(slot));
-        asm volatile("ds_read_u16 %0, %1" : "=v"(e1) : "v"(slot + 32u));
-        asm volatile("ds_read_u16 %0, %1" : "=v"(e2) : "v"(slot + 64u));
-        asm volatile("ds_read_u16 %0, %1" : "=v"(e3) : "v"(slot + 96u));
-        asm volatile("ds_read_u16 %0, %1" : "=v"(e4) : "v"(slot + 128u));
-        asm volatile("ds_read_u16 %0, %1" : "=v"(e5) : "v"(slot + 160u));
-        asm volatile("ds_read_u16 %0, %1" : "=v"(e6) : "v"(slot + 192u));
-        asm volatile("ds_read_u16 %0, %1" : "=v"(e7) : "v"(slot + 224u));
         asm volatile("ds_read_b128 %0, %1" : "=v"(ah) : "v"(za + (uint32_t)(s * 64)));
         asm volatile("ds_read_b128 %0, %1" : "=v"(al) : "v"(zb + (uint32_t)(s * 64)));
-        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(e0), "+v"(e1), "+v"(e2), "+v"(e3), "+v"(e4), "+v"(e5), "+v"(e6), "+v"(e7),
-                     "+v"(ah), "+v"(al));
-        const uint32_t r0 = e0 | (e1 << 16), r1 = e2 | (e3 << 16), r2 = e4 | (e5 << 16), r3 = e6 | (e7 << 16);
-        const u32x4_b bw = {r0, r1, r2, r3};
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_b, ah), __builtin_bit_cast(bf16x8_b, bw), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_b, al), __builtin_bit_cast(bf16x8_b, bw), acc, 0, 0, 0);
+        // eight 16-bit reads per 16-column tile into eight registers (two reads in flight into the
+        // halves of one register do not merge), packed in pairs afterwards; all four tiles' reads are
+        // issued before the one wait
+        uint32_t e[4][8];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                asm volatile("ds_read_u16 %0, %1" : "=v"(e[t][i]) : "v"(slot + (uint32_t)(t * 32 + i * 128)));
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(ah), "+v"(al),
+                     "+v"(e[0][0]), "+v"(e[0][1]), "+v"(e[0][2]), "+v"(e[0][3]), "+v"(e[0][4]), "+v"(e[0][5]), "+v"(e[0][6]), "+v"(e[0][7]),
+                     "+v"(e[1][0]), "+v"(e[1][1]), "+v"(e[1][2]), "+v"(e[1][3]), "+v"(e[1][4]), "+v"(e[1][5]), "+v"(e[1][6]), "+v"(e[1][7]));
+        asm volatile("" : "+v"(e[2][0]), "+v"(e[2][1]), "+v"(e[2][2]), "+v"(e[2][3]), "+v"(e[2][4]), "+v"(e[2][5]), "+v"(e[2][6]), "+v"(e[2][7]),
+                     "+v"(e[3][0]), "+v"(e[3][1]), "+v"(e[3][2]), "+v"(e[3][3]), "+v"(e[3][4]), "+v"(e[3][5]), "+v"(e[3][6]), "+v"(e[3][7]));
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const u32x4_b bw = {e[t][0] | (e[t][1] << 16), e[t][2] | (e[t][3] << 16), e[t][4] | (e[t][5] << 16), e[t][6] | (e[t][7] << 16)};
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_b, ah), __builtin_bit_cast(bf16x8_b, bw), acc[t], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_b, al), __builtin_bit_cast(bf16x8_b, bw), acc[t], 0, 0, 0);
+        }
     }
     __builtin_amdgcn_s_waitcnt(bt_vmcnt(0));                   // no LDS-DMA may outlive the loop
     }
 #undef BD_ISSUE
     // lane (column bq, row group q) holds rows 4q .. 4q+3 of the batch
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int b = 4 * q + i;
-        if (b < p.rows)
-            p.part[((int64_t)b * p.NR + nr) * p.d + c0 + bq] = acc[i];
-    }
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int b = 4 * q + i;
+            if (b < p.rows)
+                p.part[((int64_t)b * p.NR + nr) * p.d + c0 + t * 16 + bq] = acc[t][i];
+        }
 }
 
-// Can the batch path take this shape?  d in whole 512-element slices, at most 8 of them (one
-// wave each, 256 registers per lane), and few enough neuron pairs per workgroup for the LDS
+// Can the batch path take this shape?  d in whole 512-element slices, at most 10 of them (one
+// wave each, 168 registers per lane), and few enough neuron groups per workgroup for the LDS
 // table of Z.
 bool decode_batch_supported(int32_t d, int32_t n, bool bf16)
 {
-    if (!bf16 || d % 512 != 0 || d / 512 > 8 || n < 64)
+    if (!bf16 || d % 512 != 0 || d / 512 > 10 || n < 64)
         return false;
     const int npairs = (n + BT_G - 1) / BT_G;
     const int P = npairs < BT_MAX_WG ? npairs : BT_MAX_WG;
@@ -387,6 +397,7 @@ int decode_batch_ranges(int32_t d, int32_t n)
 {
     const int CS = d / BT_COLS;
     int NR = (256 + CS - 1) / CS;              // enough workgroups for every CU
+    if (NR > 64) NR = 64;
     const int by_range = (n + BD_RANGE - 1) / BD_RANGE;
     if (NR < by_range) NR = by_range;          // a workgroup's range of Z must fit its LDS tables
     return NR < 1 ? 1 : NR;
@@ -441,16 +452,22 @@ int launch_decode_batch_front(const DecodeJob &job, int *NR_out, hipStream_t st)
         p.x = (const uint16_t *)job.x + (int64_t)r0 * job.d;
         p.part = job.part + (size_t)r0 * NR * job.d;
         dim3 g1(p.P), b1(R * 64);
-#define BT_GO(GA, NS)                                                                                          \
+#define BT_GO2(GA, NS, MT)                                                                                     \
         {                                                                                                      \
-            if (hipFuncSetAttribute((const void *)ff_batch_gu_kernel<GA, NS, BT_G>, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                    (int)lds) != hipSuccess)                                                   \
-                return set_hip_error(hipGetLastError(), "hipFuncSetAttribute");                                \
-            hipLaunchKernelGGL((ff_batch_gu_kernel<GA, NS, BT_G>), g1, b1, lds, st, p);                              \
+            static bool attr_set_ = false;     /* raising the dynamic LDS limit is needed once per kernel */   \
+            if (!attr_set_) {                                                                                  \
+                if (hipFuncSetAttribute((const void *)ff_batch_gu_kernel<GA, NS, BT_G, MT>,                    \
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) \
+                    return set_hip_error(hipGetLastError(), "hipFuncSetAttribute");                            \
+                attr_set_ = true;                                                                              \
+            }                                                                                                  \
+            hipLaunchKernelGGL((ff_batch_gu_kernel<GA, NS, BT_G, MT>), g1, b1, lds, st, p);                    \
         }
+#define BT_GO(GA, NS) { if (R <= 8) BT_GO2(GA, NS, 512) else BT_GO2(GA, NS, 640) }
         if (gated) { if (NSTG == 4) BT_GO(true, 4) else if (NSTG == 3) BT_GO(true, 3) else BT_GO(true, 2) }
         else       { if (NSTG == 4) BT_GO(false, 4) else if (NSTG == 3) BT_GO(false, 3) else BT_GO(false, 2) }
 #undef BT_GO
+#undef BT_GO2
         int rc = check_launch("ff_batch_gu_kernel");
         if (rc != GRIFFIN_OK)
             return rc;

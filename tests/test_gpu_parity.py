@@ -79,7 +79,8 @@ def test_ff_decode_matches_oracle(dtype, d, n, act, gated, bias):
     (synth.DT_BF16, 4096, 1001, 16, True),    # matrix-core path: odd neuron count, biases
     (synth.DT_BF16, 2048, 777, 9, False),     # matrix-core path: 9 of 16 rows used
     (synth.DT_BF16, 512, 64, 40, False),      # matrix-core path: three groups of rows (16 + 16 + 8)
-    (synth.DT_BF16, 5120, 200, 16, False),    # 10 slices per row: stays on the four-rows-per-pass path
+    (synth.DT_BF16, 5120, 200, 16, False),    # matrix-core path: 10 slices per row
+    (synth.DT_BF16, 8192, 100, 8, False),     # 16 slices per row: stays on the four-rows-per-pass path
 ])
 def test_ff_decode_batch_shares_one_block(dtype, d, n, batch, bias):
     c = synth.small_case(5 + batch, d, n, 4, dtype, T=batch, with_bias=bias)
