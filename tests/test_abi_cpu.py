@@ -126,3 +126,36 @@ def test_compact_and_decode_reject_bad_arguments_without_hip():
     assert lib.griffin_topk(FAKE, 0, 10, 3, FAKE, None) == G.OK
     cu = (ctypes.c_int32 * 2)(0, 5)
     assert lib.griffin_stat_shared(None, cu, 1, 10, FAKE, None) == G.EINVAL
+
+
+def test_selectors_and_prompt_out_reject_bad_arguments_without_hip():
+    L = mk()
+    lib = G.lib
+    assert lib.griffin_weight_norm_score(ctypes.byref(L), None, None) == G.EINVAL
+    assert lib.griffin_weight_norm_score(None, FAKE, None) == G.EINVAL
+    assert G.griffin_select_sampled_workspace_bytes(1000, 10) % 256 == 0
+    assert G.griffin_select_sampled_workspace_bytes(1000, 1001) == 0
+    big = 1 << 30
+    assert lib.griffin_select_sampled(None, FAKE, 100, 10, 5, FAKE, FAKE, big, None) == G.EINVAL
+    assert lib.griffin_select_sampled(FAKE, FAKE, 100, 101, 5, FAKE, FAKE, big, None) == G.ESHAPE
+    assert lib.griffin_select_sampled(FAKE, FAKE, 100, 10, 11, FAKE, FAKE, big, None) == G.ESHAPE      # k_top > k
+    assert lib.griffin_select_sampled(FAKE, FAKE, 100, 10, 5, FAKE, None, 0, None) == G.EWORKSPACE
+    assert lib.griffin_select_sampled(FAKE, FAKE, 100, 10, 5, FAKE, FAKE, 64, None) == G.EWORKSPACE
+    assert lib.griffin_jaccard(None, 2, 10, FAKE, None) == G.EINVAL
+    assert lib.griffin_jaccard(FAKE, 0, 10, FAKE, None) == G.ESHAPE
+    assert lib.griffin_jaccard(FAKE, G.MAX_SEQS + 1, 10, FAKE, None) == G.ESHAPE
+    # prompt output: Z, ldz, tokens, d_ff, d, dtype, W2p, ldw, b2, Y, ldy, ws, ws_bytes, stream
+    po = lib.griffin_ff_prompt_out
+    assert po(None, 688, 64, 688, 256, G.F32, FAKE, 688, None, FAKE, 256, None, 0, None) == G.EINVAL
+    assert po(FAKE, 600, 64, 688, 256, G.F32, FAKE, 688, None, FAKE, 256, None, 0, None) == G.ESHAPE   # ldz < d_ff
+    assert po(FAKE, 688, 64, 688, 256, 7, FAKE, 688, None, FAKE, 256, None, 0, None) == G.EINVAL
+
+
+def test_batch_decode_workspace_covers_the_matrix_core_path():
+    # 16 rows through one block: partial rows [16][ranges][d] plus the table of Z [n][16]
+    d, n = 4096, 5504
+    need16 = G.griffin_decode_workspace_bytes(d, n, 16)
+    assert need16 >= (16 * 32 * d + n * 16) * 4
+    assert G.griffin_decode_workspace_bytes(d, n, 16) <= G.griffin_decode_workspace_bytes(d, n, 64)
+    # shapes the matrix-core path does not take keep the four-rows-per-pass size
+    assert G.griffin_decode_workspace_bytes(8192, 500, 16) == G.griffin_decode_workspace_bytes(8192, 500, 13) // 13 * 16
