@@ -7,24 +7,24 @@
 // (16 x d x n), so they run on the matrix cores; the weights are still read exactly once, so
 // the pass stays bound by HBM.  Two kernels, because the two lines want different ownership:
 //
-//  * ff_batch_gu_kernel: a workgroup of R wavefronts takes neurons two at a time, round-robin
-//    over the chip (a compact window of rows is in flight at any time).  Wave r owns the r-th
-//    512-element slice of every row: its slice of the 16 x-rows lives in registers as MFMA
-//    operand fragments (v_mfma_f32_16x16x32_bf16, x as the 16-row operand, the two neurons in
-//    two of the 16 columns), its 1 KB pieces of the Wg and W1 rows go from global memory
-//    straight into a private LDS ring (LDS-DMA, up to three neuron pairs ahead, no VGPRs),
-//    and come back as operand fragments with ds_read_b128.  Per neuron pair the waves' partial
-//    16 x 2 tiles meet in LDS (one barrier), one wave finishes sigma and the gating product,
-//    and Z goes to a small LDS table that is written out once at the end ([n][16] fp32).
-//  * ff_batch_down_kernel: the second line.  Giving every workgroup all d columns would cost
-//    one [16][d] partial per workgroup (64 MB for 256 of them), so the work is cut in two
-//    directions: a workgroup owns 256 columns and one of NR ranges of neurons, its 16 waves
-//    split the range, Z[.][j] arrives through scalar loads, the 16 x 4 accumulators per lane
-//    are fp32 FMAs, the waves' sums meet in LDS and one [16][256] partial per workgroup goes
-//    to the same partial-row buffer that the single-row path uses (NR rows per batch row).
+//  * ff_batch_gu_kernel: a workgroup of R = d/512 wavefronts takes neurons two at a time,
+//    round-robin over the chip (a compact window of rows is in flight at any time).  Wave r owns
+//    the r-th 512-element slice of every row: its slice of the 16 x-rows lives in registers as
+//    MFMA operand fragments (v_mfma_f32_16x16x32_bf16, x as the 16-row operand, the two neurons
+//    in two of the 16 columns), its 1 KB pieces of the Wg and W1 rows go from global memory
+//    straight into a private LDS ring (LDS-DMA, no VGPRs) and come back as operand fragments
+//    with ds_read_b128.  A wave keeps its partial 16 x 2 tiles in LDS; there is no barrier per
+//    group of neurons (one would tie the independent load streams to the slowest of them): the
+//    waves meet once (more often only if the tiles outgrow LDS), add the tiles in wave order,
+//    apply sigma and the gating product, and Z goes to a small LDS table that is written out at
+//    the end ([n][16] fp32).
+//  * ff_batch_down_kernel: the second line, also on the matrix cores.  Giving every workgroup all
+//    d columns would cost one [16][d] partial per workgroup (64 MB for 256 of them), so the work
+//    is cut in two directions: a workgroup owns 512 columns and one of NR ranges of neurons, and
+//    writes one [16][512] partial into the partial-row buffer that the single-row path uses
+//    (NR rows per batch row).  Details at the kernel.
 // The partial rows are then added in a fixed order by the reduce kernel of the single-row path.
 #include "common.h"
-#include <stdlib.h>
 
 namespace griffin {
 
@@ -121,13 +121,6 @@ __global__ __launch_bounds__(MAXT) void ff_batch_gu_kernel(BatchParams p)
     // LDS reads and writes below are inline asm: the compiler would make each one it knows about
     // wait for every LDS-DMA in flight, i.e. for the whole prefetch
     const uint32_t frag_off = (uint32_t)((bq & (G - 1)) * 1024 + q * 16);
-#ifdef BT_TIMING
-    uint32_t tm0 = 0, tm1 = 0, tm2 = 0, tm3 = 0, tm4 = 0, s_wait = 0, s_mfma = 0, s_bar = 0, s_sum = 0;
-    const uint32_t tstart = (uint32_t)__builtin_readcyclecounter();
-#define BT_STAMP(v) { __builtin_amdgcn_sched_barrier(0); v = (uint32_t)__builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0); }
-#else
-#define BT_STAMP(v)
-#endif
     // operand fragments of the weights, two sets: the reads of one 4-step chunk run under the MFMAs
     // of the chunk before.  Only the lanes of MFMA columns 0 .. G-1 carry a neuron; the others never
     // read (their columns of the product are never looked at) and keep zeros.
@@ -139,18 +132,8 @@ __global__ __launch_bounds__(MAXT) void ff_batch_gu_kernel(BatchParams p)
             f1[i][s] = (u32x4_b){0u, 0u, 0u, 0u};
             fg[i][s] = (u32x4_b){0u, 0u, 0u, 0u};
         }
-#ifdef BT_NOREAD
-#define BT_RDCOND (bq < G && p.n < 0)
-#else
-#define BT_RDCOND (bq < G)
-#endif
-#ifdef BT_NOMFMA
-#define BT_MMCOND (p.n < 0)
-#else
-#define BT_MMCOND true
-#endif
 #define BT_READ(F_, unit_, c_)                                                                            \
-    if (BT_RDCOND) {                                                                                       \
+    if (bq < G) {                                                                                         \
         _Pragma("unroll") for (int s = 0; s < 4; ++s)                                                     \
         {                                                                                                 \
             asm volatile("ds_read_b128 %0, %1" : "+v"(f1[F_][s]) : "v"((unit_) + (uint32_t)(((c_) * 4 + s) * 64))); \
@@ -162,7 +145,7 @@ __global__ __launch_bounds__(MAXT) void ff_batch_gu_kernel(BatchParams p)
     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f1[F_][0]), "+v"(f1[F_][1]), "+v"(f1[F_][2]), "+v"(f1[F_][3]), \
                  "+v"(fg[F_][0]), "+v"(fg[F_][1]), "+v"(fg[F_][2]), "+v"(fg[F_][3]));
 #define BT_MFMA(F_, c_)                                                                                   \
-    if (BT_MMCOND) _Pragma("unroll") for (int s = 0; s < 4; ++s)                                                     \
+    _Pragma("unroll") for (int s = 0; s < 4; ++s)                                                         \
     {                                                                                                     \
         accU = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_b, xa[(c_) * 4 + s]),    \
                                                        __builtin_bit_cast(bf16x8_b, f1[F_][s]), accU, 0, 0, 0); \
@@ -173,9 +156,7 @@ __global__ __launch_bounds__(MAXT) void ff_batch_gu_kernel(BatchParams p)
     __builtin_amdgcn_s_waitcnt(bt_vmcnt((NSTG - 2) * LPB));          // group 0 has landed
     BT_READ(0, ring_a + frag_off, 0)
     for (int t = 0; t < T; ++t) {
-        BT_STAMP(tm0)
         BT_ISSUE(t + NSTG - 1)
-        BT_STAMP(tm1)
         const uint32_t unit = ring_a + (uint32_t)((t % NSTG) * UNIT) + frag_off;
         const uint32_t unit_next = ring_a + (uint32_t)(((t + 1) % NSTG) * UNIT) + frag_off;
         f32x4_b accU = {0.f, 0.f, 0.f, 0.f}, accG = {0.f, 0.f, 0.f, 0.f};
@@ -204,7 +185,6 @@ __global__ __launch_bounds__(MAXT) void ff_batch_gu_kernel(BatchParams p)
             if (GATED)
                 asm volatile("ds_write_b128 %0, %1" :: "v"(ra + G * 16 * 4), "v"(accG) : "memory");
         }
-        BT_STAMP(tm2)
         if (te == p.TB - 1 || t == T - 1) {
             // the waves meet: partial tiles are added in wave order, sigma and the gating product follow
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -243,21 +223,7 @@ __global__ __launch_bounds__(MAXT) void ff_batch_gu_kernel(BatchParams p)
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             BT_BARRIER()                         // the partial-tile regions may be written again
         }
-        BT_STAMP(tm3)
-#ifdef BT_TIMING
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        BT_STAMP(tm4)
-        s_wait += tm1 - tm0; s_mfma += tm2 - tm1; s_bar += tm3 - tm2; s_sum += tm4 - tm3;
-        (void)tm4;
-#endif
     }
-#ifdef BT_TIMING
-    if (blockIdx.x == 0 && lane == 0) {
-        float *o = p.z + (int64_t)p.n * 16 + wave * 8;
-        o[0] = (float)s_wait / T; o[1] = (float)s_mfma / T; o[2] = (float)s_bar / T; o[3] = (float)s_sum / T;
-        o[4] = (float)((uint32_t)__builtin_readcyclecounter() - tstart); o[5] = (float)T;
-    }
-#endif
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_waitcnt(bt_vmcnt(0));          // no LDS-DMA may outlive the loop
     BT_BARRIER()
@@ -419,7 +385,6 @@ int launch_decode_batch_front(const DecodeJob &job, int *NR_out, hipStream_t st)
     const int NMAT = gated ? 2 : 1, UNIT = BT_G * NMAT * 1024;
     int NSTG = (128 * 1024) / (R * UNIT);
     if (NSTG > 4) NSTG = 4;
-    if (const char *e_ = getenv("GRIFFIN_BT_NSTG")) { int v_ = atoi(e_); if (v_ >= 2 && v_ < NSTG) NSTG = v_; }
     if (NSTG < 2)
         return GRIFFIN_EUNSUPPORTED;
     const int npairs = (job.n + BT_G - 1) / BT_G;

@@ -206,9 +206,6 @@ template <int ACT, bool GATED, int MI>
 __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass has no buffer-descriptor builtins; it only needs the launch stub
-#ifdef FF1_TIMING
-    const uint64_t tk0 = __builtin_readcyclecounter(), wk0 = wall_clock64();
-#endif
     constexpr int BM = 64 * MI, BK = 64;
     constexpr int STAGE = (BM + (GATED ? 2 : 1) * G_BN) * 8;   // 16-byte slots per stage
     constexpr int W1_SLOT = BM * 8, WG_SLOT = (BM + G_BN) * 8;
@@ -370,9 +367,6 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
         for (int r = 0; r < NREADS; ++r)
             FF1_READ_ONE(0, r, sa, sb)
     }
-#ifdef FF1_TIMING
-    const uint64_t tk1 = __builtin_readcyclecounter();
-#endif
     for (int kt = 0; kt < KT; ++kt) {
         const uint32_t st_cur = lds0 + (uint32_t)((kt & 1) * STAGE * 16);
         const uint32_t st_nxt = lds0 + (uint32_t)(((kt + 1) & 1) * STAGE * 16);
@@ -399,19 +393,7 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
 #undef FF1_WAIT_FRAGS
 #undef FF1_KSTEP
 
-#ifdef FF1_TIMING
-    const uint64_t tk2 = __builtin_readcyclecounter();
-#endif
     ff1_mfma_epilogue_t<ACT, GATED, MI>(p, accU, accG, rs, lds0, m0, n0, tile_n);
-#ifdef FF1_TIMING
-    __syncthreads();
-    const uint64_t tk3 = __builtin_readcyclecounter(), wk3 = wall_clock64();
-    if ((logical == 0 || logical == nblk - 1) && tid == 0) {
-        float *q = p.Z + (logical == 0 ? 0 : 64);
-        q[0] = (float)(tk1 - tk0); q[1] = (float)(tk2 - tk1); q[2] = (float)(tk3 - tk2); q[3] = (float)(wk3 - wk0);
-        q[4] = (float)KT;
-    }
-#endif
 #endif
 }
 
