@@ -80,16 +80,29 @@ __global__ __launch_bounds__(256) void col_stat_kernel(const float *Z, int64_t l
 }
 
 // s[seq][j] = sqrt(sum_chunk s2part[seq][chunk][j]) in ascending chunk order
-__global__ __launch_bounds__(256) void stat_finalize_kernel(const float *s2part, int rc, int F, float *s,
-                                                            float *s_out)
+// (one wavefront per 64 columns so that the few columns still fill the chip; eight loads in flight
+// per lane, added in chunk order)
+__global__ __launch_bounds__(64) void stat_finalize_kernel(const float *s2part, int rc, int F, float *s,
+                                                           float *s_out)
 {
     const int seq = blockIdx.y;
-    const int j = blockIdx.x * 256 + threadIdx.x;
+    const int j = blockIdx.x * 64 + threadIdx.x;
     if (j >= F)
         return;
+    const float *p = s2part + (int64_t)seq * rc * F + j;
     float acc = 0.0f;
-    for (int c = 0; c < rc; ++c)
-        acc += s2part[((int64_t)seq * rc + c) * F + j];
+    int c = 0;
+    for (; c + 8 <= rc; c += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            v[u] = p[(int64_t)(c + u) * F];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            acc += v[u];
+    }
+    for (; c < rc; ++c)
+        acc += p[(int64_t)c * F];
     const float v = sqrtf(acc);
     s[(int64_t)seq * F + j] = v;
     if (s_out)
@@ -144,7 +157,7 @@ int launch_stat(const float *Z, int64_t ldz, const float *rowpart, int nt, int64
     }
     if ((rcode = check_launch("col_stat_kernel")) != GRIFFIN_OK)
         return rcode;
-    hipLaunchKernelGGL(stat_finalize_kernel, dim3((F + 255) / 256, seqs.n), dim3(256), 0, st, s2part, rc, F, s, s_out);
+    hipLaunchKernelGGL(stat_finalize_kernel, dim3((F + 63) / 64, seqs.n), dim3(64), 0, st, s2part, rc, F, s, s_out);
     return check_launch("stat_finalize_kernel");
 }
 

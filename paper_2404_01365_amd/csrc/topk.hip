@@ -49,11 +49,17 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *s
     return sh[wave] + inc - v;
 }
 
+// CACHED: the row's keys are read from global memory once (coalesced, eight loads in flight per
+// thread) into LDS and every later pass works from there; without it each of the five passes
+// pays the global-memory latency of its loads again, one after the other.
+constexpr int TOPK_CACHE_KEYS = 36864;       // 144 KB of LDS
+
+template <bool CACHED>
 __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(const float *scores, int n, int k,
                                                                    int32_t *idx_out)
 {
+    __shared__ uint32_t keys[CACHED ? TOPK_CACHE_KEYS : 1];
     __shared__ uint32_t hist[256];
-    __shared__ uint32_t suffix[2][257];
     __shared__ uint32_t sh_digit, sh_need;
     __shared__ uint32_t sh_scan[TOPK_THREADS / 64 + 1];
 
@@ -61,42 +67,73 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(const float *
     int32_t *out = idx_out + (int64_t)blockIdx.x * k;
     const int tid = threadIdx.x;
 
+    if (CACHED) {
+        int i = tid;
+        for (; i + 7 * TOPK_THREADS < n; i += 8 * TOPK_THREADS) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                v[u] = row[i + u * TOPK_THREADS];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                keys[i + u * TOPK_THREADS] = order_key(v[u]);
+        }
+        for (; i < n; i += TOPK_THREADS)
+            keys[i] = order_key(row[i]);
+        __syncthreads();
+    }
+#define TOPK_KEY(i_) (CACHED ? keys[i_] : order_key(row[i_]))
+
     uint32_t prefix = 0, mask = 0, need = (uint32_t)k;
     for (int pass = 0; pass < 4; ++pass) {
         const int shift = 24 - 8 * pass;
         if (tid < 256)
             hist[tid] = 0;
         __syncthreads();
-        for (int i = tid; i < n; i += TOPK_THREADS) {
-            const uint32_t key = order_key(row[i]);
-            if ((key & mask) == prefix)
-                atomicAdd(&hist[(key >> shift) & 255u], 1u);
-        }
-        __syncthreads();
-        // suffix sums S[b] = sum_{b' >= b} hist[b'] (Hillis-Steele over 256 bins), S[256] = 0
-        if (tid < 256)
-            suffix[0][tid] = hist[tid];
-        if (tid == 0) {
-            suffix[0][256] = 0;
-            suffix[1][256] = 0;
-        }
-        __syncthreads();
-        int cur = 0;
-        for (int off = 1; off < 256; off <<= 1) {
-            if (tid < 256) {
-                uint32_t v = suffix[cur][tid];
-                if (tid + off < 256)
-                    v += suffix[cur][tid + off];
-                suffix[cur ^ 1][tid] = v;
+        // the statistic's values sit in a narrow range, so in the first passes most keys of a wave
+        // share one digit: lanes that agree with the wave's first candidate send ONE atomic with
+        // their count, the others go singly
+        for (int i0 = 0; i0 < n; i0 += TOPK_THREADS) {
+            const int i = i0 + tid;
+            uint32_t key = 0;
+            bool cand = false;
+            if (i < n) {
+                key = TOPK_KEY(i);
+                cand = (key & mask) == prefix;
             }
-            __syncthreads();
-            cur ^= 1;
+            const uint32_t digit = (key >> shift) & 255u;
+            const uint64_t cmask = __ballot(cand);
+            if (cmask != 0) {
+                const int leader = __builtin_ctzll(cmask);
+                const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)digit, leader);
+                const uint64_t same = __ballot(cand && digit == d0);
+                if ((int)(tid & 63) == leader)
+                    atomicAdd(&hist[d0], (uint32_t)__builtin_popcountll(same));
+                else if (cand && digit != d0)
+                    atomicAdd(&hist[digit], 1u);
+            }
         }
-        // the digit of the k-th largest: the one bin with S[b] >= need > S[b+1]
-        if (tid < 256) {
-            const uint32_t here = suffix[cur][tid], above = suffix[cur][tid + 1];
-            if (here >= need && above < need) {
-                sh_digit = (uint32_t)tid;
+        __syncthreads();
+        // the digit of the k-th largest: the one bin b with S[b] >= need > S[b+1], S[b] = sum of the
+        // bins b' >= b.  One wavefront: lane l owns bins 4l .. 4l+3, suffix sums across lanes by shuffles.
+        if (tid < 64) {
+            const uint32_t h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2], h3 = hist[4 * tid + 3];
+            const uint32_t loc = h0 + h1 + h2 + h3;
+            uint32_t suf = loc;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t t = __shfl_down(suf, off, 64);
+                if (tid + off < 64)
+                    suf += t;
+            }
+            const uint32_t s4 = suf - loc, s3 = s4 + h3, s2 = s3 + h2, s1 = s2 + h1, s0 = s1 + h0;
+            if (s0 >= need && s4 < need) {
+                uint32_t dg, above;
+                if (s3 >= need) { dg = 3; above = s4; }
+                else if (s2 >= need) { dg = 2; above = s3; }
+                else if (s1 >= need) { dg = 1; above = s2; }
+                else { dg = 0; above = s1; }
+                sh_digit = 4u * tid + dg;
                 sh_need = need - above;
             }
         }
@@ -113,7 +150,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(const float *
     const int lo = min(tid * chunk, n), hi = min(lo + chunk, n);
     uint32_t c_gt = 0, c_eq = 0;
     for (int i = lo; i < hi; ++i) {
-        const uint32_t key = order_key(row[i]);
+        const uint32_t key = TOPK_KEY(i);
         c_gt += key > tau;
         c_eq += key == tau;
     }
@@ -121,7 +158,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(const float *
     uint32_t p_gt = block_exclusive_scan(c_gt, sh_scan, tot_gt);
     uint32_t p_eq = block_exclusive_scan(c_eq, sh_scan, tot_eq);
     for (int i = lo; i < hi; ++i) {
-        const uint32_t key = order_key(row[i]);
+        const uint32_t key = TOPK_KEY(i);
         if (key > tau) {
             out[p_gt + min(p_eq, need)] = i;
             ++p_gt;
@@ -131,11 +168,15 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(const float *
             ++p_eq;
         }
     }
+#undef TOPK_KEY
 }
 
 int launch_topk(const float *scores, int32_t n_rows, int32_t n, int32_t k, int32_t *idx, hipStream_t st)
 {
-    hipLaunchKernelGGL(topk_select_kernel, dim3(n_rows), dim3(TOPK_THREADS), 0, st, scores, n, k, idx);
+    if (n <= TOPK_CACHE_KEYS)
+        hipLaunchKernelGGL(topk_select_kernel<true>, dim3(n_rows), dim3(TOPK_THREADS), 0, st, scores, n, k, idx);
+    else
+        hipLaunchKernelGGL(topk_select_kernel<false>, dim3(n_rows), dim3(TOPK_THREADS), 0, st, scores, n, k, idx);
     return check_launch("topk_select_kernel");
 }
 

@@ -180,7 +180,8 @@ def test_indexed_and_multi_decode_match_compact_decode():
 
 
 # ------------------------------------------------------------------ top-k
-@pytest.mark.parametrize("n,k", [(1, 1), (7, 3), (64, 64), (688, 344), (1000, 1), (5000, 4999), (24576, 12288)])
+@pytest.mark.parametrize("n,k", [(1, 1), (7, 3), (64, 64), (688, 344), (1000, 1), (5000, 4999), (24576, 12288),
+                                 (8200, 4100), (36864, 20000), (40000, 777)])   # 8 loads + tail; the largest cached row; uncached
 def test_topk_matches_oracle(n, k):
     rng = np.random.default_rng(n * 31 + k)
     rows = 3
