@@ -126,6 +126,10 @@ int launch_jaccard(const int32_t *idx, int32_t n_sets, int32_t k, float *out, hi
 int launch_compact(const griffin_layer &L, const int32_t *idx, int32_t k, const griffin_layer &C,
                    hipStream_t st);
 
+bool gemm_nt_partials_ok(int64_t M, int32_t N, int32_t K, int64_t lda, int64_t ldb);
+void gemm_nt_split_plan(int64_t M, int32_t N, int32_t K, int *splits, int *kt_per_split);
+int launch_gemm_nt_partials(const void *A, int64_t lda, const void *B, int64_t ldb, int64_t M, int32_t N, int32_t K,
+                            int splits, int kt_per_split, float *C, hipStream_t st);
 int launch_ff2(const float *Z, int64_t ldz, int64_t M, int32_t F, int32_t d, bool bf16, const void *W2p,
                int64_t ldw, const void *b2, void *Y, int64_t ldy, float *ws, size_t ws_bytes, hipStream_t st);
 size_t ff2_workspace_bytes(int64_t M, int32_t F, int32_t d);

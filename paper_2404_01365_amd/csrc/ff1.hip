@@ -33,6 +33,7 @@ struct Ff1Params {
     float *Z, *rowpart;
     int64_t ldx, ldw, ldz;
     int32_t M, F, d, nt, mt;
+    int32_t splits, kt_per_split;    // ranges of the contraction (1 for the activations) and 64-wide k-tiles per range
 };
 
 // Epilogue shared by the MFMA kernels: sigma, gating, store of Z, row sums of z^2.
@@ -95,7 +96,9 @@ __device__ __forceinline__ void ff1_mfma_epilogue(const Ff1Params &p, f32x16 (&a
 // four partials per token, one per (wn, lh), meet in LDS).
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
-template <int ACT, bool GATED, int MI>
+// PLAIN: the kernel serves as a plain C = A B^T with fp32 output (one range of a split contraction):
+// no activation, no biases, no row sums; Z points at that range's [M][F] slab.
+template <int ACT, bool GATED, int MI, bool PLAIN>
 __device__ __forceinline__ void ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (&accU)[MI][2], f32x16 (&accG)[MI][2],
                                                     float (*rs)[64 * MI], uint32_t stage_lds, int m0, int n0, int tile_n)
 {
@@ -103,7 +106,7 @@ __device__ __forceinline__ void ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1, l31 = lane & 31, lh = lane >> 5;
     const bool vec = ((p.F | (int32_t)p.ldz) & 3) == 0 && ((uintptr_t)p.Z & 15) == 0;
-    const bool hb = p.b1 != nullptr || (GATED && p.bg != nullptr);
+    const bool hb = !PLAIN && (p.b1 != nullptr || (GATED && p.bg != nullptr));
     const uint16_t *b1p = (const uint16_t *)p.b1, *bgp = (const uint16_t *)p.bg;
     if (vec && !hb) {
         // The usual case (no biases, 16-byte aligned rows of Z, F a multiple of 4).  A wave's
@@ -129,7 +132,7 @@ __device__ __forceinline__ void ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const float u = accU[mi][ni][g * 4 + e];
-                        v[e] = GATED ? act_apply_t<ACT>(accG[mi][ni][g * 4 + e]) * u : act_apply_t<ACT>(u);
+                        v[e] = PLAIN ? u : (GATED ? act_apply_t<ACT>(accG[mi][ni][g * 4 + e]) * u : act_apply_t<ACT>(u));
                     }
                     if (n0 + wn * 64 + ni * 32 + g * 8 + lh * 4 >= p.F)
                         v = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
@@ -167,9 +170,9 @@ __device__ __forceinline__ void ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
                     const int cj = min(col, p.F - 1);
                     float u = accU[mi][ni][i];
                     float gt = GATED ? accG[mi][ni][i] : 0.0f;
-                    if (b1p) u += bf16_bits_to_f32(b1p[cj]);
-                    if (GATED && bgp) gt += bf16_bits_to_f32(bgp[cj]);
-                    const float z = GATED ? act_apply_t<ACT>(gt) * u : act_apply_t<ACT>(u);
+                    if (!PLAIN && b1p) u += bf16_bits_to_f32(b1p[cj]);
+                    if (!PLAIN && GATED && bgp) gt += bf16_bits_to_f32(bgp[cj]);
+                    const float z = PLAIN ? u : (GATED ? act_apply_t<ACT>(gt) * u : act_apply_t<ACT>(u));
                     if (col < p.F) {
                         sq = fmaf(z, z, sq);
                         if (rowok)
@@ -180,6 +183,8 @@ __device__ __forceinline__ void ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
             rs[wn * 2 + lh][lrow] = sq;
         }
     }
+    if (PLAIN)
+        return;
     __syncthreads();
     for (int r = tid; r < BM; r += G_THREADS)
         if (m0 + r < p.M)
@@ -202,7 +207,7 @@ __device__ __forceinline__ void ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
 // dead stage, which keeps the loop body branch-free.
 typedef __attribute__((address_space(3))) void lds_void_t;
 
-template <int ACT, bool GATED, int MI>
+template <int ACT, bool GATED, int MI, bool PLAIN>
 __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass has no buffer-descriptor builtins; it only needs the launch stub
@@ -215,14 +220,17 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
     __shared__ u32x4 lds[2 * STAGE];
     __shared__ float rs[4][BM];
 
-    // XCD-aware tile order
-    const int nblk = p.mt * p.nt;
+    // XCD-aware tile order; with a split contraction the ranges of one tile are `ntile` ids apart
+    const int ntile = p.mt * p.nt, nblk = ntile * p.splits;
     const int per_xcd = (nblk + 7) / 8;
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (logical >= nblk)
         return;
-    const int tile_n = logical / p.mt, tile_m = logical % p.mt;
+    const int split = logical / ntile, tile = logical % ntile;
+    const int tile_n = tile / p.mt, tile_m = tile % p.mt;
     const int m0 = tile_m * BM, n0 = tile_n * G_BN;
+    if (PLAIN)
+        p.Z += (int64_t)split * p.M * p.ldz;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -247,13 +255,14 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
         (void *)((const uint16_t *)p.W1 + (int64_t)n0 * p.ldw), 0, RSRC_RECORDS, RSRC_FLAGS);
     const __amdgpu_buffer_rsrc_t rWg = __builtin_amdgcn_make_buffer_rsrc(
         (void *)((const uint16_t *)(GATED ? p.Wg : p.W1) + (int64_t)n0 * p.ldw), 0, RSRC_RECORDS, RSRC_FLAGS);
-    const int KT = p.d / BK;
+    const int kt0 = split * p.kt_per_split;
+    const int KT = min(p.kt_per_split, p.d / BK - kt0);      // k-tiles of this range (>= 1 by construction)
 
 // LDS-DMA instruction number q (0 .. NLOADS-1: the X regions, then W1, then Wg) of k-tile kt_
 #define FF1_LOAD_ONE(kt_, q)                                                                             \
     {                                                                                                    \
         u32x4 *st_ = lds + ((kt_) & 1) * STAGE;                                                          \
-        const int so_ = min((kt_), KT - 1) * (BK * 2);                                                   \
+        const int so_ = (kt0 + min((kt_), KT - 1)) * (BK * 2);                                           \
         if ((q) < XQ)                                                                                    \
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rX, (lds_void_t *)(st_ + (wave * XQ + (q) % XQ) * 64), 16, \
                                                      xvo[(q) % XQ], so_, 0, 0);                          \
@@ -393,7 +402,7 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
 #undef FF1_WAIT_FRAGS
 #undef FF1_KSTEP
 
-    ff1_mfma_epilogue_t<ACT, GATED, MI>(p, accU, accG, rs, lds0, m0, n0, tile_n);
+    ff1_mfma_epilogue_t<ACT, GATED, MI, PLAIN>(p, accU, accG, rs, lds0, m0, n0, tile_n);
 #endif
 }
 
@@ -644,10 +653,10 @@ static void launch_mfma(const Ff1Params &p, bool gated, hipStream_t st)
     const bool ktail = p.d % 64 != 0 || p.ldx > (1 << 21) || p.ldw > (1 << 21);
     if (gated) {
         if (ktail) hipLaunchKernelGGL((ff1_bf16_mfma_staged_kernel<ACT, true, MI, true>), grid, block, 0, st, p);
-        else hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, true, MI>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, true, MI, false>), grid, block, 0, st, p);
     } else {
         if (ktail) hipLaunchKernelGGL((ff1_bf16_mfma_staged_kernel<ACT, false, MI, true>), grid, block, 0, st, p);
-        else hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, false, MI>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, false, MI, false>), grid, block, 0, st, p);
     }
 }
 
@@ -669,6 +678,7 @@ int launch_ff1(const griffin_layer &L, const void *X, int64_t ldx, int64_t M, fl
     p.Z = Z; p.rowpart = rowpart;
     p.ldx = ldx; p.ldw = L.ld; p.ldz = ldz;
     p.M = (int32_t)M; p.F = L.n; p.d = L.d;
+    p.splits = 1; p.kt_per_split = L.d / 64;
     p.nt = ff1_ntiles(L);
     *nt_out = p.nt;
     if (M == 0)
@@ -692,6 +702,61 @@ int launch_ff1(const griffin_layer &L, const void *X, int64_t ldx, int64_t M, fl
     else
         hipLaunchKernelGGL(ff1_f32_kernel<false>, grid, block, 0, st, p, L.act);
     return check_launch("ff1_f32_kernel");
+}
+
+// C[s] = A B^T over the s-th range of the contraction, fp32, for s = 0 .. splits-1, on the
+// direct-to-LDS kernel: A [M][K] and B [N][K] bf16 with K a multiple of 64, C [splits][M][N].
+// Used by the prompt-output GEMM (Section 5.1) on a bf16 copy of Z.
+bool gemm_nt_partials_ok(int64_t M, int32_t N, int32_t K, int64_t lda, int64_t ldb)
+{
+    return M >= 1 && M <= (1 << 30) && K % 64 == 0 && N % 4 == 0 && lda % 8 == 0 && ldb % 8 == 0 &&
+           lda <= (1 << 21) && ldb <= (1 << 21);
+}
+
+void gemm_nt_split_plan(int64_t M, int32_t N, int32_t K, int *splits, int *kt_per_split)
+{
+    const int bm = M > 128 ? 256 : 128;
+    const int64_t ntile = ((M + bm - 1) / bm) * ((N + G_BN - 1) / G_BN);
+    const int KT = K / 64;
+    int best = 1;
+    int64_t best_cost = -1;
+    for (int s = 1; s <= 16 && s <= KT; ++s) {
+        const int per = (KT + s - 1) / s;
+        if (s > 1 && per < 16)
+            break;
+        const int used = (KT + per - 1) / per;
+        const int64_t rounds = (ntile * used + 255) / 256;
+        const int64_t cost = rounds * (per + 8);           // 8 k-tiles' worth of prologue and epilogue per item
+        if (best_cost < 0 || cost < best_cost) {
+            best_cost = cost;
+            best = s;
+        }
+    }
+    const int per = (KT + best - 1) / best;
+    *splits = (KT + per - 1) / per;
+    *kt_per_split = per;
+}
+
+int launch_gemm_nt_partials(const void *A, int64_t lda, const void *B, int64_t ldb, int64_t M, int32_t N, int32_t K,
+                            int splits, int kt_per_split, float *C, hipStream_t st)
+{
+    Ff1Params p;
+    p.X = A; p.Wg = nullptr; p.W1 = B; p.bg = nullptr; p.b1 = nullptr;
+    p.Z = C; p.rowpart = nullptr;
+    p.ldx = lda; p.ldw = ldb; p.ldz = N;
+    p.M = (int32_t)M; p.F = N; p.d = K;
+    p.splits = splits; p.kt_per_split = kt_per_split;
+    p.nt = (N + G_BN - 1) / G_BN;
+    if (M > 128) {
+        p.mt = (int32_t)((M + 255) / 256);
+        const int nblk = p.mt * p.nt * splits;
+        hipLaunchKernelGGL((ff1_bf16_mfma_kernel<GRIFFIN_ACT_RELU, false, 4, true>), dim3(((nblk + 7) / 8) * 8), dim3(G_THREADS), 0, st, p);
+    } else {
+        p.mt = (int32_t)((M + 127) / 128);
+        const int nblk = p.mt * p.nt * splits;
+        hipLaunchKernelGGL((ff1_bf16_mfma_kernel<GRIFFIN_ACT_RELU, false, 2, true>), dim3(((nblk + 7) / 8) * 8), dim3(G_THREADS), 0, st, p);
+    }
+    return check_launch("ff1_bf16_mfma_kernel");
 }
 
 }  // namespace griffin

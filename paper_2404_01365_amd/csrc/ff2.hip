@@ -230,6 +230,28 @@ __global__ __launch_bounds__(256) void ff2_plain_kernel(Ff2Params p)
     store_scalar<BF16>(p.Y, (int64_t)row * p.ldy + col, acc);
 }
 
+// Z fp32 -> bf16 copy [M][F] (rounded to nearest even), 8 elements per thread
+__global__ __launch_bounds__(256) void ff2_z_to_bf16_kernel(const float *Z, int64_t ldz, int64_t M, int32_t F, uint16_t *Zb)
+{
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;       // F is a multiple of 64 on this path
+    if (i >= M * F)
+        return;
+    const int64_t row = i / F;
+    const int col = (int)(i % F);
+    const f32x4 a = *(const f32x4 *)(Z + row * ldz + col), b = *(const f32x4 *)(Z + row * ldz + col + 4);
+    u32x4 o;
+    o.x = pack_bf16(a.x, a.y); o.y = pack_bf16(a.z, a.w); o.z = pack_bf16(b.x, b.y); o.w = pack_bf16(b.z, b.w);
+    *(u32x4 *)(Zb + i) = o;
+}
+
+static inline size_t ff2_align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// the direct-to-LDS GEMM takes the shape when D_ff comes in whole 64-wide k-tiles
+static bool ff2_dma_ok(const float *Z, int64_t ldz, int64_t M, int32_t F, int32_t d, bool bf16, const void *W2p, int64_t ldw)
+{
+    return bf16 && ldz % 4 == 0 && (((uintptr_t)Z | (uintptr_t)W2p) & 15) == 0 && gemm_nt_partials_ok(M, d, F, F, ldw);
+}
+
 static bool ff2_tiles_ok(const float *Z, int64_t ldz, int32_t F, int32_t d, bool bf16, const void *W2p, int64_t ldw)
 {
     return bf16 && F % 8 == 0 && d % 4 == 0 && ldz % 4 == 0 && ldw % 8 == 0 &&
@@ -254,7 +276,15 @@ size_t ff2_workspace_bytes(int64_t M, int32_t F, int32_t d)
 {
     int splits, per;
     ff2_split_plan(M, F, d, &splits, &per);
-    return splits > 1 ? (size_t)splits * M * d * sizeof(float) : 0;
+    size_t need = splits > 1 ? (size_t)splits * M * d * sizeof(float) : 0;
+    if (M >= 1 && F % 64 == 0 && d % 4 == 0) {
+        // direct-to-LDS path: a bf16 copy of Z, then one fp32 slab per range of the contraction
+        gemm_nt_split_plan(M, d, F, &splits, &per);
+        const size_t dma = ff2_align256((size_t)M * F * 2) + (size_t)splits * M * d * sizeof(float);
+        if (dma > need)
+            need = dma;
+    }
+    return need;
 }
 
 int launch_ff2(const float *Z, int64_t ldz, int64_t M, int32_t F, int32_t d, bool bf16, const void *W2p,
@@ -267,6 +297,25 @@ int launch_ff2(const float *Z, int64_t ldz, int64_t M, int32_t F, int32_t d, boo
     p.ldz = ldz; p.ldw = ldw; p.ldy = ldy;
     p.M = (int32_t)M; p.F = F; p.d = d;
     p.splits = 1; p.kt_per_split = (F + P_BK - 1) / P_BK;
+    if (ff2_dma_ok(Z, ldz, M, F, d, bf16, W2p, ldw)) {
+        int per;
+        gemm_nt_split_plan(M, d, F, &p.splits, &per);
+        const size_t zb_bytes = ff2_align256((size_t)M * F * 2);
+        if (!ws || ((uintptr_t)ws & 15) || ws_bytes < zb_bytes + (size_t)p.splits * M * d * sizeof(float))
+            return GRIFFIN_EWORKSPACE;
+        uint16_t *Zb = (uint16_t *)ws;
+        p.part = (float *)((char *)ws + zb_bytes);
+        const int64_t oct = M * F / 8;
+        hipLaunchKernelGGL(ff2_z_to_bf16_kernel, dim3((unsigned)((oct + 255) / 256)), dim3(256), 0, st, Z, ldz, M, F, Zb);
+        int rc = check_launch("ff2_z_to_bf16_kernel");
+        if (rc != GRIFFIN_OK)
+            return rc;
+        if ((rc = launch_gemm_nt_partials(Zb, F, W2p, ldw, M, d, F, p.splits, per, p.part, st)) != GRIFFIN_OK)
+            return rc;
+        const int64_t quads = (int64_t)M * d / 4;
+        hipLaunchKernelGGL(ff2_split_sum_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, p);
+        return check_launch("ff2_split_sum_kernel");
+    }
     if (ff2_tiles_ok(Z, ldz, F, d, bf16, W2p, ldw)) {
         ff2_split_plan(M, F, d, &p.splits, &p.kt_per_split);
         if (p.splits > 1 && (!ws || ws_bytes < ff2_workspace_bytes(M, F, d) || ((uintptr_t)ws & 15)))

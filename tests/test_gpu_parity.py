@@ -332,7 +332,10 @@ def test_shared_set_for_a_batch_end_to_end():
 # ------------------------------------------------------------------ the prompt's own output (full block)
 @pytest.mark.parametrize("dtype,d,F,S,bias", [
     (synth.DT_BF16, 512, 1000, 300, True),     # MFMA tiles, ragged in every dimension
-    (synth.DT_BF16, 256, 4096, 40, True),      # long contraction cut into ranges
+    (synth.DT_BF16, 256, 4096, 40, True),      # direct-to-LDS GEMM, 128-token tile, contraction cut into 4 ranges
+    (synth.DT_BF16, 384, 2048, 300, False),    # direct-to-LDS GEMM, two ragged 256-token tiles
+    (synth.DT_BF16, 520, 1024, 130, True),     # direct-to-LDS GEMM, last feature tile 8 wide
+    (synth.DT_BF16, 256, 4104, 40, True),      # D_ff not in whole 64-wide k-tiles: register-staged GEMM, ranges
     (synth.DT_BF16, 136, 264, 70, False),      # k tail (264 = 4 * 64 + 8)
     (synth.DT_BF16, 64, 131, 9, True),         # D_ff not a multiple of 8: plain path
     (synth.DT_F32, 256, 688, 64, True),        # config-0 shape, fp32
