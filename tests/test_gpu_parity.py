@@ -413,3 +413,62 @@ def test_jaccard_of_selected_sets_matches_oracle():
     ref = np.array([[oracle.jaccard(sets[a], sets[b]) for b in range(B)] for a in range(B)])
     np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=1e-6)
     assert out[0, 1].item() == 1.0 and np.allclose(np.diag(out.cpu().numpy()), 1.0)
+
+
+# ------------------------------------------------------------------ the documented maxima
+def test_prefill_takes_the_maximum_number_of_sequences():
+    """GRIFFIN_MAX_SEQS prompts in one call: lengths 0..5, many of them empty."""
+    dtype, d, F, k = synth.DT_BF16, 64, 96, 24
+    rng = np.random.default_rng(21)
+    lens = rng.integers(0, 6, size=G.MAX_SEQS).tolist()
+    lens[0], lens[-1] = 0, 5
+    c = synth.small_case(77, d, F, sum(lens), dtype)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    L, _ = dev_layer(c["Wg"], c["W1"], c["W2"], synth.ACT_SILU, dtype)
+    idx, s, Z = run_prefill(L, to_dev(c["X"], dtype), cu, k)
+    Z_ref = oracle.ff1(c["X"], c["Wg"], c["W1"], synth.ACT_SILU)
+    assert max_rel(Z, Z_ref) <= TOL_Z
+    for b in range(G.MAX_SEQS):
+        if lens[b] == 0:
+            assert np.all(s[b] == 0.0) and idx[b].tolist() == list(range(k))
+            continue
+        s_ref = oracle.stat(Z_ref[cu[b]:cu[b + 1]])
+        assert np.max(np.abs(s[b] - s_ref)) <= TOL_S * np.max(s_ref)
+        if boundary_report(s_ref, k)[0] > 1e-3:
+            np.testing.assert_array_equal(idx[b], oracle.topk(s_ref, k))
+        else:       # the boundary is too tight to pin the set: what is selected must still be a top-k of the device's own s
+            assert np.min(s[b][idx[b]]) >= np.max(np.delete(s[b], idx[b])) - 1e-12
+
+
+def test_decode_takes_the_maximum_batch():
+    """GRIFFIN_MAX_BATCH rows: per-row index lists, per-row compact blocks, one shared block."""
+    dtype, d, n, k, B = synth.DT_BF16, 512, 200, 64, G.MAX_BATCH
+    c = synth.small_case(31, d, n, 4, dtype, T=B)
+    L, t = dev_layer(c["Wg"], c["W1"], c["W2"], synth.ACT_SILU, dtype)
+    rng = np.random.default_rng(5)
+    idx = np.stack([np.sort(rng.choice(n, k, replace=False)) for _ in range(B)]).astype(np.int32)
+    idx_dev = torch.from_numpy(idx).cuda()
+    x = to_dev(c["xt"], dtype)
+    ws = workspace(max(G.griffin_decode_workspace_bytes(d, k, B), G.griffin_decode_workspace_bytes(d, n, B)))
+    y = torch.empty_like(x)
+    G.griffin_ff_decode_indexed(L, idx_dev, k, B, x, y, workspace=ws)
+    sync()
+    y_idx = to_host(y)
+    Cs, keep = [], []
+    for b in range(B):
+        C, ct = empty_compact(L, k, t)
+        G.griffin_compact(L, idx_dev[b], k, C)
+        Cs.append(C); keep.append(ct)
+    y2 = torch.empty_like(x)
+    G.griffin_ff_decode_multi(Cs, x, y2, workspace=ws)
+    sync()
+    y_multi = to_host(y2)
+    y3 = torch.empty_like(x)
+    G.griffin_ff_decode(L, x, y3, B, workspace=ws)          # all rows through the full block (Eq. 1)
+    sync()
+    y_full = to_host(y3)
+    for b in range(0, B, 7):
+        ref = oracle.ff_decode(c["xt"][b], c["Wg"][idx[b]], c["W1"][idx[b]], c["W2"][idx[b]], synth.ACT_SILU)
+        assert max_rel(y_idx[b], ref) <= TOL_OUT[dtype] and max_rel(y_multi[b], ref) <= TOL_OUT[dtype]
+        assert max_rel(y_full[b], oracle.ff_decode(c["xt"][b], c["Wg"], c["W1"], c["W2"], synth.ACT_SILU)) <= TOL_OUT[dtype]
+    assert np.array_equal(y_idx, y_multi)
