@@ -54,6 +54,10 @@ struct BatchParams {
     int32_t TB;              // groups between two meetings of the first kernel's waves
 };
 
+// cache policy of the weight stream: read once, so non-temporal (135 MB in a bare LDS-DMA read
+// loop: 20.4 us against 23.3 us with the default policy)
+constexpr int BT_NT = 2;
+
 constexpr int bt_vmcnt(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 
 template <bool GATED, int NSTG, int G, int MAXT>
@@ -102,9 +106,9 @@ __global__ __launch_bounds__(MAXT) void ff_batch_gu_kernel(BatchParams p)
         _Pragma("unroll") for (int g_ = 0; g_ < G; ++g_)                                                  \
         {                                                                                                 \
             const int64_t r_ = (int64_t)min(G * pr_ + g_, p.n - 1) * p.ld;                                \
-            __builtin_amdgcn_global_load_lds((gbl_cvoid_b *)(w1p + r_), (lds_void_b *)(sl_ + g_ * 1024), 16, 0, 0); \
+            __builtin_amdgcn_global_load_lds((gbl_cvoid_b *)(w1p + r_), (lds_void_b *)(sl_ + g_ * 1024), 16, 0, BT_NT); \
             if (GATED)                                                                                    \
-                __builtin_amdgcn_global_load_lds((gbl_cvoid_b *)(wgp + r_), (lds_void_b *)(sl_ + (G + g_) * 1024), 16, 0, 0); \
+                __builtin_amdgcn_global_load_lds((gbl_cvoid_b *)(wgp + r_), (lds_void_b *)(sl_ + (G + g_) * 1024), 16, 0, BT_NT); \
         }                                                                                                 \
     }
 #define BT_BARRIER()                                                                                      \
@@ -293,7 +297,7 @@ __global__ __launch_bounds__(BT_WAVES2 * 64) void ff_batch_down_kernel(BatchPara
     {                                                                                                        \
         const int row_ = min(j_lo + min((s_), S - 1) * 32 + u * 8 + lrow, p.n - 1);                          \
         __builtin_amdgcn_global_load_lds((gbl_cvoid_b *)(w2 + (int64_t)row_ * p.ld),                         \
-                                         (lds_void_b *)(ring + ((s_) % BD_DEPTH) * 256 + u * 64), 16, 0, 0); \
+                                         (lds_void_b *)(ring + ((s_) % BD_DEPTH) * 256 + u * 64), 16, 0, BT_NT); \
     }
     f32x4_b acc[4];
 #pragma unroll
