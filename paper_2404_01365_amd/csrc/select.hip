@@ -2,7 +2,8 @@
 //
 //  * weight_norm_kernel: the static score of the paper's magnitude baseline (Section 5.1,
 //    "Setup"): ||W1_j||_2, times ||Wg_j||_2 for GLU blocks.  One wavefront per neuron, 16-byte
-//    loads, fp32 sums: a single pass over 2*F*d weights, bandwidth-bound.
+//    non-temporal loads (the weights pass once), fp32 sums: a single pass over 2*F*d weights,
+//    bandwidth-bound.
 //  * sample_score_kernel / sample_mark_kernel: sampling-based selection (Appendix B).  Weighted
 //    sampling without replacement is run as exponential clocks: neuron j rings at e_j / s_j with
 //    e_j a unit exponential variate supplied by the caller; the earliest rings win.  The order
@@ -30,7 +31,7 @@ __global__ __launch_bounds__(256) void weight_norm_kernel(const void *W1, const 
         const uint16_t *r1 = (const uint16_t *)W1 + (int64_t)j * ld;
         const uint16_t *rg = Wg ? (const uint16_t *)Wg + (int64_t)j * ld : nullptr;
         for (int c = lane * 8; c < d; c += 512) {       // d is a multiple of 8
-            const u32x4_s v = *(const u32x4_s *)(r1 + c);
+            const u32x4_s v = __builtin_nontemporal_load((const u32x4_s *)(r1 + c));
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const float lo = __uint_as_float(v[t] << 16), hi = __uint_as_float(v[t] & 0xFFFF0000u);
@@ -38,7 +39,7 @@ __global__ __launch_bounds__(256) void weight_norm_kernel(const void *W1, const 
                 a = fmaf(hi, hi, a);
             }
             if (rg) {
-                const u32x4_s g = *(const u32x4_s *)(rg + c);
+                const u32x4_s g = __builtin_nontemporal_load((const u32x4_s *)(rg + c));
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const float lo = __uint_as_float(g[t] << 16), hi = __uint_as_float(g[t] & 0xFFFF0000u);
