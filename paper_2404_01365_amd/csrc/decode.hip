@@ -127,10 +127,6 @@ __device__ __forceinline__ void decode_body(const DecodeParams &p, const void *W
     constexpr int NV = 2 * G * NB;                   // values to combine across the team per step
     float(*myred)[2 * G * DEC_NB_MAX][16] = red + team * 2;   // [parity][value][wave of the team]
 
-    // zero the padding entries of the cross-wave buffers once
-    for (int i = threadIdx.x; i < p.teams * 2 * 2 * G * DEC_NB_MAX * 16; i += blockDim.x)
-        (&red[0][0][0])[i] = 0.0f;
-    __syncthreads();
 
     // Loads are branch-free (slots past the last neuron re-read the last row, which stays in
     // L2, and are masked when z is formed) so that the compiler can wait for exactly the
@@ -201,8 +197,13 @@ __device__ __forceinline__ void decode_body(const DecodeParams &p, const void *W
         }                                                                                    \
     }
 
-    if (nsteps > 0) {
+    if (nsteps > 0)
         DEC_LOAD(0, 0)
+    // zero the padding entries of the cross-wave buffers once (the first rows are already on their way)
+    for (int i = threadIdx.x; i < p.teams * 2 * 2 * G * DEC_NB_MAX * 16; i += blockDim.x)
+        (&red[0][0][0])[i] = 0.0f;
+    __syncthreads();
+    if (nsteps > 0) {
         int s = 0;
         while (s + 2 < nsteps) {
             DEC_LOAD(1, s + 1)
