@@ -31,7 +31,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=1, help="workload: index into BASELINE.json configs (1, 2 or 3)")
+    ap.add_argument("--config", type=int, default=1, help="workload: 1 Llama-2-7B-shaped layer, 2 Gemma-7B-shaped layer, 3 Llama-2-13B-shaped stack of 40")
     ap.add_argument("--k", type=int, default=0, help="kept neurons (default: the config's 50%% point)")
     ap.add_argument("--layers", type=int, default=0, help="layers to run (default: all of the config)")
     ap.add_argument("--probe-every", type=int, default=8, help="decode steps between kernel-duration probes")
@@ -103,7 +103,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU; --gpus %d is not supported (the path shards by "
-              "layer or by sequence with no communication, see DESIGN.md)" % args.gpus, file=sys.stderr)
+              "layer or by sequence with no communication)" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
