@@ -40,6 +40,9 @@ def parse():
                     help="do not time the full-width block after the timed region (keeps a profile's per-kernel "
                          "averages to the pruned launches only)")
     ap.add_argument("--warm", action="store_true", help="single copy of the compact weights (cache-warm)")
+    ap.add_argument("--layout", choices=("rows", "transposed"), default="rows",
+                    help="compact block: W2 neuron-major (one stream plus a kernel that adds 256 partial rows, default) or "
+                         "output-feature-major (two pure streams per token, no partial rows)")
     return ap.parse_args()
 
 
@@ -148,13 +151,23 @@ def main():
         n_rep = 1
     else:
         n_rep = -(-(1 << 30) // (n_layers * compact_bytes))
+    transposed = args.layout == "transposed" and cfg.dtype == synth.DT_BF16 and d % 512 == 0
+    ldt = -(-k // 512) * 512
+    ldt_full = -(-F // 512) * 512
     for t in layers:
         t["C"], t["Ct"] = [], []
         for r in range(n_rep):
-            # the three rows of a kept neuron side by side: [k][3][d], row stride 3d
-            blk = torch.empty((k, 3, d), dtype=tdt, device="cuda")
-            t["Ct"].append(blk)
-            t["C"].append(G.layer(blk[:, 1], blk[:, 2], blk[:, 0], act=cfg.act))
+            if transposed:
+                # Wg and W1 rows of a kept neuron side by side ([k][2][d]); W2 output-feature-major [d][ldt]
+                blk = torch.empty((k, 2, d), dtype=tdt, device="cuda")
+                w2t = torch.empty((d, ldt), dtype=tdt, device="cuda")
+                t["Ct"].append((blk, w2t))
+                t["C"].append(G.layer(blk[:, 1], None, blk[:, 0], act=cfg.act, W2t=w2t, n=k, d=d))
+            else:
+                # the three rows of a kept neuron side by side: [k][3][d], row stride 3d
+                blk = torch.empty((k, 3, d), dtype=tdt, device="cuda")
+                t["Ct"].append(blk)
+                t["C"].append(G.layer(blk[:, 1], blk[:, 2], blk[:, 0], act=cfg.act))
         t["idx"] = torch.empty((1, k), dtype=torch.int32, device="cuda")
         t["y"] = torch.empty((T, d), dtype=tdt, device="cuda")
     ws_pre = torch.empty(G.griffin_prefill_workspace_bytes(layers[0]["L"], S, 1, False), dtype=torch.uint8, device="cuda")
@@ -217,12 +230,17 @@ def main():
     fe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     full_bytes = 3 * F * d * w
     n_full = 1 if (args.warm or args.skip_full_width or n_layers * full_bytes >= (1 << 30)) else -(-(1 << 30) // (n_layers * full_bytes))
+    def full_w2t(W2):
+        out = torch.zeros((d, ldt_full), dtype=tdt, device="cuda")     # the paper's W_2, zero-padded (plumbing, untimed)
+        out[:, :F] = W2.t()
+        return out
     for t in layers:
-        t["Lf"], t["Lft"] = [t["L"]], []
-        for r in range(1, n_full):
-            cp = (t["Wg"].clone(), t["W1"].clone(), t["W2"].clone())
-            t["Lft"].append(cp)
-            t["Lf"].append(G.layer(cp[1], cp[2], cp[0], act=cfg.act))
+        t["Lf"], t["Lft"] = [], []
+        for r in range(0 if args.skip_full_width else n_full):
+            cp = (t["Wg"], t["W1"], t["W2"]) if r == 0 else (t["Wg"].clone(), t["W1"].clone(), t["W2"].clone())
+            w2t = full_w2t(cp[2]) if transposed else None
+            t["Lft"].append((cp, w2t))
+            t["Lf"].append(G.layer(cp[1], cp[2], cp[0], act=cfg.act, W2t=w2t))
     for rep in range(0 if args.skip_full_width else 2):
         if rep == 1:
             fe[0].record()
@@ -235,7 +253,7 @@ def main():
         torch.cuda.synchronize()
         full_us = fe[0].elapsed_time(fe[1]) * 1e3 / (T * n_layers)
         for t in layers:
-            t["Lf"], t["Lft"] = [t["L"]], []
+            t["Lf"], t["Lft"] = [], []
 
     # the prompt's own full-width output Y = Z W_2^T (Section 5.1), outside the timed region
     prompt_out_us = None
@@ -269,6 +287,16 @@ def main():
             G.griffin_weight_norm_score(t0l["L"], sc, stream=stream)
         ev[1].record()
         Bsh = 16
+        if transposed:
+            # the batch path streams W2 neuron-major: blocks [k][3][d] of the same selection, made outside the timing
+            rows_keep, rows_C = [], []
+            for r in range(n_rep):
+                blk = torch.empty((k, 3, d), dtype=tdt, device="cuda")
+                Cr = G.layer(blk[:, 1], blk[:, 2], blk[:, 0], act=cfg.act)
+                G.griffin_compact(t0l["L"], t0l["idx"], k, Cr, stream=stream)
+                rows_keep.append(blk); rows_C.append(Cr)
+        else:
+            rows_C = t0l["C"]
         xb = t0l["xt"][:Bsh].contiguous()
         yb = torch.empty_like(xb)
         ws_b = torch.empty(G.griffin_decode_workspace_bytes(d, k, Bsh), dtype=torch.uint8, device="cuda")
@@ -277,7 +305,7 @@ def main():
             if rep == 1:
                 ev[2].record()
             for r in range(reps_b):
-                G.griffin_ff_decode(t0l["C"][r % n_rep], xb, yb, Bsh, workspace=ws_b, stream=stream)
+                G.griffin_ff_decode(rows_C[r % n_rep], xb, yb, Bsh, workspace=ws_b, stream=stream)
         ev[3].record()
         torch.cuda.synchronize()
         wn_us = ev[0].elapsed_time(ev[1]) * 1e3 / 5
@@ -305,14 +333,23 @@ def main():
     kern_us = sorted(max(v - event_overhead_us, 0.0) for v in raw_main)
     avg_us = sum(kern_us) / len(kern_us)
     raw_us = raw_main
-    alg_bytes = 3 * k * d * w + 2 * d * w           # compact weights once + x in + y out
-    achieved = alg_bytes / (avg_us * 1e-6) / 1e9
+    alg_bytes = 3 * k * d * w + 2 * d * w           # one layer-token: compact weights once + x in + y out
+    if transposed:
+        # the timed kernel streams Wg and W1 of the kept neurons, reads x, writes z (fp32, padded)
+        kern_name, kern_bytes = "ff_decode_gu_kernel", 2 * k * d * w + d * w + ldt * 4
+    else:
+        kern_name, kern_bytes = "ff_decode_kernel", alg_bytes
+    achieved = kern_bytes / (avg_us * 1e-6) / 1e9
+    # the second kernel of a token: the W2 stream (transposed layout) or the sum of the partial rows
+    raw_second = [hip.elapsed_ms(m, e) * 1e3 for a, m, e in probes]
+    second_us = max(sum(raw_second) / len(raw_second) - event_overhead_us, 0.0)
+    second_bytes = (ldt * d * w + ldt * 4 + d * w) if transposed else None
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as fh:
-            traffic = json.load(fh).get("config%d_k%d" % (cfg.cid, k))
+            traffic = json.load(fh).get("config%d_k%d%s" % (cfg.cid, k, "_gu" if transposed else ""))
 
     out = {
         "metric": "pruned-FF decode tokens/s + achieved HBM GB/s; select us/layer (prefill)",
@@ -327,13 +364,14 @@ def main():
             "workload": "config %d: %s, d=%d D_ff=%d, prompt %d tokens, keep k=%d, batch 1, %d decode steps, %d layer(s)"
                         % (cfg.cid, cfg.name, d, F, S, k, T, n_layers),
             "compact_weight_copies_cycled": n_rep,
+            "compact_layout": "Wg,W1 [k][2][d] + W2 output-feature-major [d][%d]" % ldt if transposed else "Wg,W1,W2 [k][3][d]",
             "cache": "warm (one copy)" if n_rep == 1 and n_layers * compact_bytes < (1 << 30) else "cold (>= 1 GiB cycled)",
         },
         "roofline": {
-            "bound": "hbm", "kernel": "ff_decode_kernel",
+            "bound": "hbm", "kernel": kern_name,
             "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": traffic,
-            "algorithmic_bytes_per_launch": alg_bytes,
+            "algorithmic_bytes_per_launch": kern_bytes,
             "avg_kernel_us": avg_us, "median_kernel_us": kern_us[len(kern_us) // 2], "launches_timed": len(kern_us),
             "raw_event_span_us": sum(raw_us) / len(raw_us), "event_cost_us": event_overhead_us,
             "unprobed_us_per_layer_token": u,
@@ -342,6 +380,8 @@ def main():
             "tokens_per_s_decode_only": T / (dec_ms * 1e-3),
             "us_per_layer_token": dec_ms * 1e3 / (T * n_layers),
             "GBps_per_layer_token": alg_bytes / (dec_ms * 1e-3 / (T * n_layers)) / 1e9,
+            "second_kernel": {"name": "ff_decode_down_kernel" if transposed else "ff_decode_reduce_kernel", "avg_us": second_us,
+                              "GBps": None if second_bytes is None else second_bytes / (second_us * 1e-6) / 1e9},
             "full_width_us_per_layer_token": full_us, "full_width_copies_cycled": n_full,
             "pruned_over_full_latency": (u / full_us) if full_us else None,
         },

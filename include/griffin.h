@@ -17,6 +17,7 @@
  *   - dtype is the storage type of X, x, y and of all weights and biases (fp32 or bf16).
  *     Accumulation, activations, Z, the statistic s and the selection run in fp32.
  *   - d must be a multiple of 8; d, n <= 2^20; ld >= d and a multiple of 8 (16-byte rows).
+ *   - A block may carry W2 a second time in the paper's own orientation (W2t, see griffin_layer).
  */
 #ifndef GRIFFIN_H
 #define GRIFFIN_H
@@ -61,6 +62,14 @@ typedef struct {
     const void *bg;   /* [n] or NULL */
     const void *b1;   /* [n] or NULL */
     const void *b2;   /* [d] or NULL */
+    const void *W2t;  /* optional second copy of W2, output-feature-major: [d][ldt], row c holding
+                         W2[0..n-1][c] (this IS the paper's W_2, D x n) followed by zeros up to
+                         ldt.  When a block has it, griffin_ff_decode and griffin_ff_decode_multi
+                         stream it instead of W2 for single rows, which lets every workgroup finish
+                         its own output features (no partial rows); such a block may leave W2 NULL
+                         if nothing else reads it.  griffin_compact fills it when the target
+                         block has it.  bf16 blocks with d a multiple of 512 only. */
+    int64_t ldt;      /* row stride of W2t in elements: a multiple of 512, >= n; 0 without W2t */
 } griffin_layer;
 
 const char *griffin_status_string(int status);
@@ -149,7 +158,9 @@ int griffin_jaccard(const int32_t *idx, int32_t n_sets, int32_t k, float *out, v
 
 /*
  * Compaction (Section 4.2; Eq. 4-5): C->Wg/W1/W2 row t <- L row idx[t], C->bg/b1 entry t <-
- * L entry idx[t]; b2 is not touched (the caller passes L->b2 as C->b2).  C describes
+ * L entry idx[t]; b2 is not touched (the caller passes L->b2 as C->b2).  If C->W2t is given,
+ * C->W2t[c][t] <- L->W2[idx[t]][c] as well (columns k .. C->ldt-1 are zeroed), and C->W2 may be
+ * NULL; L->W2 is always the source.  C describes
  * caller-allocated device buffers: C->n == k, C->d == L->d, same dtype and act, C->ld >= d.
  * A matrix or bias that is NULL in L must be NULL in C.  idx [k] int32 device, each in
  * [0, L->n); the kernel clamps out-of-range entries instead of faulting.

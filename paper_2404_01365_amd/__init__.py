@@ -35,6 +35,7 @@ class griffin_layer(ctypes.Structure):
         ("Wg", ctypes.c_void_p), ("W1", ctypes.c_void_p), ("W2", ctypes.c_void_p),
         ("ld", ctypes.c_int64),
         ("bg", ctypes.c_void_p), ("b1", ctypes.c_void_p), ("b2", ctypes.c_void_p),
+        ("W2t", ctypes.c_void_p), ("ldt", ctypes.c_int64),
     ]
 
 
@@ -115,8 +116,9 @@ def _check(status: int, where: str) -> None:
 
 
 def layer(W1, W2, Wg=None, *, act: int, dtype: Optional[int] = None, bg=None, b1=None, b2=None,
-          d: Optional[int] = None, n: Optional[int] = None, ld: Optional[int] = None) -> griffin_layer:
-    """Describe one FF block held in torch tensors ([n][d] neuron-major, contiguous rows)."""
+          d: Optional[int] = None, n: Optional[int] = None, ld: Optional[int] = None, W2t=None) -> griffin_layer:
+    """Describe one FF block held in torch tensors ([n][d] neuron-major, contiguous rows).
+    W2t: optional [d][ldt] copy of W2 in the paper's orientation (W2 may then be None)."""
     import torch
     if dtype is None:
         dtype = BF16 if W1.dtype == torch.bfloat16 else F32
@@ -127,8 +129,10 @@ def layer(W1, W2, Wg=None, *, act: int, dtype: Optional[int] = None, bg=None, b1
     L.dtype, L.act = dtype, act
     L.Wg, L.W1, L.W2 = _ptr(Wg), _ptr(W1), _ptr(W2)
     L.bg, L.b1, L.b2 = _ptr(bg), _ptr(b1), _ptr(b2)
+    L.W2t = _ptr(W2t)
+    L.ldt = 0 if W2t is None else W2t.stride(0)
     # keep the tensors alive as long as the descriptor
-    L._keep = (W1, W2, Wg, bg, b1, b2)
+    L._keep = (W1, W2, Wg, bg, b1, b2, W2t)
     return L
 
 

@@ -29,7 +29,7 @@ constexpr int32_t MAX_DIM = 1 << 20;
 // shape/pointer checks common to every entry point that takes a block description
 static int check_layer(const griffin_layer *L)
 {
-    if (!L || !L->W1 || !L->W2)
+    if (!L || !L->W1 || (!L->W2 && !L->W2t))
         return GRIFFIN_EINVAL;
     if (L->dtype != GRIFFIN_F32 && L->dtype != GRIFFIN_BF16)
         return GRIFFIN_EINVAL;
@@ -43,6 +43,12 @@ static int check_layer(const griffin_layer *L)
         return GRIFFIN_ESHAPE;
     if (!L->Wg && L->bg)
         return GRIFFIN_EINVAL;
+    if (L->W2t) {       // the second, output-feature-major copy of W2: bf16, whole 512-element slices
+        if (L->dtype != GRIFFIN_BF16)
+            return GRIFFIN_EUNSUPPORTED;
+        if (L->d % 512 != 0 || L->ldt < L->n || L->ldt % 512 != 0 || L->ldt > 2 * (int64_t)MAX_DIM || !aligned16(L->W2t))
+            return GRIFFIN_ESHAPE;
+    }
     return GRIFFIN_OK;
 }
 
@@ -248,7 +254,7 @@ int griffin_compact(const griffin_layer *L, const int32_t *idx, int32_t k, const
         return rc;
     if ((rc = check_layer(C)) != GRIFFIN_OK)
         return rc;
-    if (!idx)
+    if (!idx || !L->W2)            // the neuron-major W2 of the full block is the source
         return GRIFFIN_EINVAL;
     if (k < 1 || k > L->n || C->n != k || C->d != L->d || C->dtype != L->dtype || C->act != L->act)
         return GRIFFIN_ESHAPE;
@@ -321,6 +327,7 @@ static int decode_common(const griffin_layer *L0, const griffin_layer *multi, co
     job.bf16 = L0->dtype == GRIFFIN_BF16;
     job.ld = L0->ld;
     job.Wg = L0->Wg; job.W1 = L0->W1; job.W2 = L0->W2; job.bg = L0->bg; job.b1 = L0->b1; job.b2 = L0->b2;
+    job.W2t = L0->W2t; job.ldt = L0->ldt;
     job.multi = multi;
     job.idx = idx; job.n_src = L0->n;
     job.x = x; job.y = y;

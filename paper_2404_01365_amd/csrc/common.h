@@ -140,6 +140,8 @@ struct DecodeJob {
     int64_t ld;
     // single block (all rows) ...
     const void *Wg, *W1, *W2, *bg, *b1, *b2;
+    const void *W2t;         // optional output-feature-major copy of W2, [d][ldt]
+    int64_t ldt;
     // ... or one block per row (host array of `batch` layers), or an index list into one block
     const griffin_layer *multi;
     const int32_t *idx;      // [batch][n] rows of the full block, or NULL
@@ -150,6 +152,9 @@ struct DecodeJob {
     size_t part_bytes;
 };
 int launch_decode(const DecodeJob &job, hipStream_t st);
+// one row through a block that carries W2t: two pure streams, no partial rows (decode_split.hip)
+bool decode_split_supported(const DecodeJob &job);
+int launch_decode_split(const DecodeJob &job, hipStream_t st, hipEvent_t ev_mid);
 // rows 5.. of a batch through one shared block: matrix-core path (decode_batch.hip)
 bool decode_batch_supported(int32_t d, int32_t n, bool bf16);
 size_t decode_batch_workspace_floats(int32_t d, int32_t n, int32_t batch);

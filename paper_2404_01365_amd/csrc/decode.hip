@@ -389,6 +389,14 @@ int launch_decode(const DecodeJob &job, hipStream_t st)
     if (ev_begin && hipEventRecord(ev_begin, st) != hipSuccess)
         return set_hip_error(hipGetLastError(), "hipEventRecord");
 
+    if (decode_split_supported(job)) {
+        int rc = launch_decode_split(job, st, ev_mid);
+        if (rc == GRIFFIN_OK && ev_end && hipEventRecord(ev_end, st) != hipSuccess)
+            return set_hip_error(hipGetLastError(), "hipEventRecord");
+        return rc;
+    }
+    if (!job.W2 && !job.multi)
+        return GRIFFIN_EUNSUPPORTED;       // only the transposed copy is there and this call cannot use it
     if (batch_path) {
         int rc = launch_decode_batch_front(job, &P, st);
         if (rc != GRIFFIN_OK)

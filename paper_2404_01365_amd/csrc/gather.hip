@@ -31,6 +31,48 @@ __global__ __launch_bounds__(256) void compact_rows_kernel(GatherParams p)
         o[c] = s[c];
 }
 
+// The second copy of the compact W2, output-feature-major (the paper's own orientation of W_2):
+// W2t[c][t] = W2[idx[t]][c] for t < k, zero for k <= t < ldt.  A workgroup moves a 64-neuron x
+// 64-feature tile through LDS: 128-byte pieces of 64 gathered rows in, 128-byte pieces of 64
+// feature rows out (bf16 only, d a multiple of 64, ldt a multiple of 64).
+__global__ __launch_bounds__(256) void compact_transpose_kernel(const uint16_t *W2, int64_t ld, int n_src,
+                                                                const int32_t *idx, int k, uint16_t *W2t, int64_t ldt)
+{
+    __shared__ uint16_t tile[64][66];            // [neuron][feature], padded
+    const int t0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    const int tid = threadIdx.x;
+    // in: thread (row r = tid >> 2 (+0), quarter q = tid & 3) reads 16 features of one gathered row
+    {
+        const int r = tid >> 2, q = tid & 3;
+        const int t = t0 + r;
+        uint32_t v[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+        if (t < k) {
+            int row = idx[t];
+            row = row < 0 ? 0 : (row >= n_src ? n_src - 1 : row);
+            const uint4 *src = (const uint4 *)(W2 + (int64_t)row * ld + c0 + q * 16);
+            const uint4 a = src[0], b = src[1];
+            v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            tile[r][q * 16 + 2 * e] = (uint16_t)(v[e] & 0xFFFFu);
+            tile[r][q * 16 + 2 * e + 1] = (uint16_t)(v[e] >> 16);
+        }
+    }
+    __syncthreads();
+    // out: thread (feature c = tid >> 2, quarter q) writes 16 neurons of one feature row
+    {
+        const int c = tid >> 2, q = tid & 3;
+        uint32_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            v[e] = (uint32_t)tile[q * 16 + 2 * e][c] | ((uint32_t)tile[q * 16 + 2 * e + 1][c] << 16);
+        uint4 *dst = (uint4 *)(W2t + (int64_t)(c0 + c) * ldt + t0 + q * 16);
+        dst[0] = make_uint4(v[0], v[1], v[2], v[3]);
+        dst[1] = make_uint4(v[4], v[5], v[6], v[7]);
+    }
+}
+
 __global__ __launch_bounds__(256) void compact_bias_kernel(GatherParams p)
 {
     const int t = blockIdx.x * 256 + threadIdx.x;
@@ -55,6 +97,8 @@ int launch_compact(const griffin_layer &L, const int32_t *idx, int32_t k, const 
     const int es = L.dtype == GRIFFIN_BF16 ? 2 : 4;
     p.src[0] = L.Wg; p.src[1] = L.W1; p.src[2] = L.W2;
     p.dst[0] = (void *)C.Wg; p.dst[1] = (void *)C.W1; p.dst[2] = (void *)C.W2;
+    if (!C.W2)
+        p.src[2] = nullptr;        // the target keeps W2 only in its transposed copy
     p.bsrc[0] = L.bg; p.bsrc[1] = L.b1;
     p.bdst[0] = (void *)C.bg; p.bdst[1] = (void *)C.b1;
     p.idx = idx;
@@ -66,6 +110,13 @@ int launch_compact(const griffin_layer &L, const int32_t *idx, int32_t k, const 
     int rc = check_launch("compact_rows_kernel");
     if (rc != GRIFFIN_OK)
         return rc;
+    if (C.W2t) {
+        dim3 grid((unsigned)(C.ldt / 64), L.d / 64);
+        hipLaunchKernelGGL(compact_transpose_kernel, grid, dim3(256), 0, st, (const uint16_t *)L.W2, L.ld, L.n, idx, k,
+                           (uint16_t *)C.W2t, C.ldt);
+        if ((rc = check_launch("compact_transpose_kernel")) != GRIFFIN_OK)
+            return rc;
+    }
     if (L.bg || L.b1) {
         hipLaunchKernelGGL(compact_bias_kernel, dim3((k + 255) / 256), dim3(256), 0, st, p);
         rc = check_launch("compact_bias_kernel");

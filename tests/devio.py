@@ -33,11 +33,27 @@ def dev_layer(Wg, W1, W2, act, dtype, bg=None, b1=None, b2=None):
     return L, t
 
 
-def empty_compact(L, k, tensors, interleaved=False):
+def empty_compact(L, k, tensors, interleaved=False, transposed=None):
     """Caller-allocated compact block for k neurons of L.  `interleaved` stores the three rows
-    of a neuron side by side ([k][3][d], row stride 3d) instead of three separate matrices."""
+    of a neuron side by side ([k][3][d], row stride 3d) instead of three separate matrices.
+    `transposed`: "both" adds the output-feature-major copy W2t [d][ldt] next to W2, "only" keeps
+    W2 in that form alone (Wg and W1 then sit side by side, [k][2][d], when interleaved)."""
     W1 = tensors["W1"]
     vec = lambda src: None if src is None else torch.empty((k,), dtype=W1.dtype, device="cuda")
+    if transposed:
+        ldt = -(-k // 512) * 512
+        W2t = torch.full((L.d, ldt), float("nan"), dtype=W1.dtype, device="cuda")
+        if transposed == "only":
+            if interleaved:
+                blk = torch.empty((k, 2, L.d), dtype=W1.dtype, device="cuda")
+                mats = dict(Wg=None if tensors["Wg"] is None else blk[:, 0], W1=blk[:, 1], W2=None)
+            else:
+                mk = lambda: torch.empty((k, L.d), dtype=W1.dtype, device="cuda")
+                mats = dict(Wg=None if tensors["Wg"] is None else mk(), W1=mk(), W2=None)
+            c = dict(mats, bg=vec(tensors["bg"]), b1=vec(tensors["b1"]), b2=tensors["b2"], W2t=W2t)
+            C = G.layer(c["W1"], None, c["Wg"], act=L.act, dtype=L.dtype, bg=c["bg"], b1=c["b1"], b2=c["b2"],
+                        W2t=W2t, n=k, d=L.d)
+            return C, c
     if interleaved:
         blk = torch.empty((k, 3, L.d), dtype=W1.dtype, device="cuda")
         mats = dict(Wg=None if tensors["Wg"] is None else blk[:, 0], W1=blk[:, 1], W2=blk[:, 2])
@@ -45,7 +61,10 @@ def empty_compact(L, k, tensors, interleaved=False):
         mk = lambda: torch.empty((k, L.d), dtype=W1.dtype, device="cuda")
         mats = dict(Wg=None if tensors["Wg"] is None else mk(), W1=mk(), W2=mk())
     c = dict(mats, bg=vec(tensors["bg"]), b1=vec(tensors["b1"]), b2=tensors["b2"])
-    C = G.layer(c["W1"], c["W2"], c["Wg"], act=L.act, dtype=L.dtype, bg=c["bg"], b1=c["b1"], b2=c["b2"])
+    if transposed:
+        c["W2t"] = W2t
+    C = G.layer(c["W1"], c["W2"], c["Wg"], act=L.act, dtype=L.dtype, bg=c["bg"], b1=c["b1"], b2=c["b2"],
+                W2t=c.get("W2t"))
     return C, c
 
 

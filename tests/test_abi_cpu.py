@@ -27,9 +27,10 @@ def test_every_declared_symbol_is_exported_and_bound():
 
 
 def test_struct_layout_matches_header():
-    # 4 x int32, 3 pointers, int64, 3 pointers
-    assert ctypes.sizeof(G.griffin_layer) == 16 + 24 + 8 + 24
+    # 4 x int32, 3 pointers, int64, 3 pointers, pointer, int64
+    assert ctypes.sizeof(G.griffin_layer) == 16 + 24 + 8 + 24 + 16
     assert G.griffin_layer.ld.offset == 40 and G.griffin_layer.b2.offset == 64
+    assert G.griffin_layer.W2t.offset == 72 and G.griffin_layer.ldt.offset == 80
 
 
 def test_status_strings_and_version():

@@ -116,6 +116,43 @@ def test_ff_decode_batch_matrix_core_path_layouts(gated, interleaved):
         assert max_rel(got[b], ref) <= TOL_OUT[synth.DT_BF16], b
 
 
+# ------------------------------------------------------------------ blocks that carry W2 in the paper's orientation
+@pytest.mark.parametrize("d,n,k,gated,bias,mode,interleaved", [
+    (1024, 700, 333, True, False, "only", True),      # k not a multiple of anything, two teams... of two waves
+    (4096, 600, 600, True, True, "both", False),      # keep all, biases, eight waves per team
+    (512, 2000, 1025, False, True, "only", False),    # Eq. 2 block, one wave per team, padding of 511 columns
+    (5120, 300, 64, True, False, "only", True),       # ten waves per team
+    (3072, 1000, 512, True, False, "both", True),     # k exactly one slice
+])
+def test_decode_through_transposed_w2_matches_oracle(d, n, k, gated, bias, mode, interleaved):
+    dtype, act = synth.DT_BF16, synth.ACT_SILU
+    c = synth.small_case(d + n + k, d, n, 4, dtype, T=3, with_bias=bias)
+    Wg = c["Wg"] if gated else None
+    bg = c.get("bg") if gated else None
+    L, t = dev_layer(Wg, c["W1"], c["W2"], act, dtype, bg, c.get("b1"), c.get("b2"))
+    idx_h = np.sort(np.random.default_rng(k).choice(n, k, replace=False)).astype(np.int32)
+    idx = torch.from_numpy(idx_h).cuda()
+    C, ct = empty_compact(L, k, t, interleaved=interleaved, transposed=mode)
+    G.griffin_compact(L, idx, k, C)
+    sync()
+    # the transposed copy is the gathered W2 turned round, bit for bit, zero-padded
+    W2t = ct["W2t"].view(torch.int16).cpu().numpy().view(np.uint16)
+    ref_bits = synth.bf16_bits(c["W2"][idx_h]).T
+    assert np.array_equal(W2t[:, :k], ref_bits) and not W2t[:, k:].any()
+    sub = lambda a: None if a is None else a[idx_h]
+    for step in range(3):
+        got = run_decode(C, to_dev(c["xt"][step], dtype))
+        ref = oracle.ff_decode(c["xt"][step], sub(Wg), c["W1"][idx_h], c["W2"][idx_h], act, sub(bg), sub(c.get("b1")), c.get("b2"))
+        assert max_rel(got, ref) <= TOL_OUT[dtype], step
+    if mode == "both":
+        # a batch of rows through the same block takes the neuron-major copy
+        xb = to_dev(c["xt"], dtype)
+        gotb = run_decode(C, xb, batch=3)
+        for b in range(3):
+            ref = oracle.ff_decode(c["xt"][b], sub(Wg), c["W1"][idx_h], c["W2"][idx_h], act, sub(bg), sub(c.get("b1")), c.get("b2"))
+            assert max_rel(gotb[b], ref) <= TOL_OUT[dtype]
+
+
 # ------------------------------------------------------------------ compaction
 @pytest.mark.parametrize("interleaved", [False, True])
 @pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
