@@ -14,9 +14,10 @@
 //     per matrix (one window in all when the three rows of a neuron are stored side by
 //     side, i.e. Wg, W1, W2 interleaved with ld = 3d);
 //   * the two dot products are reduced inside the wave with DPP, combined across the team's
-//     waves through a few LDS words and one barrier per G neurons, and the next G neurons'
-//     loads are already in flight while that happens (register double buffer; the loads are
-//     branch-free so the compiler waits for the older buffer only);
+//     waves through a few LDS words and one barrier per G neurons, and the loads of the next
+//     two steps are already in flight while that happens (three register sets; the loads are
+//     branch-free so the compiler waits for the oldest set only; with one step of lookahead a
+//     wave streams only one step's bytes per memory latency, which is what bounds narrow rows);
 //   * each workgroup folds its teams' y slabs in LDS (one team for rows of 4 KB and more) and
 //     writes one fp32 partial row; a second tiny kernel adds the partial rows in a fixed
 //     order (deterministic), adds b2 and converts to the output type.
@@ -131,9 +132,9 @@ __device__ __forceinline__ void decode_body(const DecodeParams &p, const void *W
     // Loads are branch-free (slots past the last neuron re-read the last row, which stays in
     // L2, and are masked when z is formed) so that the compiler can wait for exactly the
     // older buffer while the newer one is still in flight.
-    u32x4 buf[2][G][3];
-    int rows[2][G];
-    float bias[2][G][2];
+    u32x4 buf[3][G][3];
+    int rows[3][G];
+    float bias[3][G][2];
 
 // the weights are read once per call: non-temporal loads (no allocation in the caches on the way)
 // stream measurably faster than plain ones (135 MB: 20.4 us against 24.0 us in a bare read loop)
@@ -197,28 +198,25 @@ __device__ __forceinline__ void decode_body(const DecodeParams &p, const void *W
         }                                                                                    \
     }
 
-    if (nsteps > 0)
+    if (nsteps > 0) {
         DEC_LOAD(0, 0)
+        DEC_LOAD(1, 1)             // steps past the end re-read the last row and contribute nothing
+    }
     // zero the padding entries of the cross-wave buffers once (the first rows are already on their way)
     for (int i = threadIdx.x; i < p.teams * 2 * 2 * G * DEC_NB_MAX * 16; i += blockDim.x)
         (&red[0][0][0])[i] = 0.0f;
     __syncthreads();
-    if (nsteps > 0) {
-        int s = 0;
-        while (s + 2 < nsteps) {
-            DEC_LOAD(1, s + 1)
-            DEC_CONSUME(0, s)
-            DEC_LOAD(0, s + 2)
-            DEC_CONSUME(1, s + 1)
-            s += 2;
-        }
-        if (s + 1 < nsteps) {
-            DEC_LOAD(1, s + 1)
-            DEC_CONSUME(0, s)
-            DEC_CONSUME(1, s + 1)
-        } else {
-            DEC_CONSUME(0, s)
-        }
+    for (int s = 0; s < nsteps; s += 3) {
+        DEC_LOAD(2, s + 2)
+        DEC_CONSUME(0, s)
+        if (s + 1 >= nsteps)
+            break;
+        DEC_LOAD(0, s + 3)
+        DEC_CONSUME(1, s + 1)
+        if (s + 2 >= nsteps)
+            break;
+        DEC_LOAD(1, s + 4)
+        DEC_CONSUME(2, s + 2)
     }
 #undef DEC_LOAD
 #undef DEC_STREAM_LOAD
