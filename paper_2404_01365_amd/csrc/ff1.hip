@@ -197,15 +197,20 @@ __device__ __forceinline__ void ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
 // cache line per row: with half lines the other half is evicted from the 32 KB vector L1
 // before the next k-tile asks for it, every line crosses the L2->L1 path twice and that path
 // (64 B/clk) becomes the bound.  An instruction covers 8 rows x 128 B.  Two LDS stages; a row
-// of a stage is 8 slots, logical chunk c of row r in slot c ^ (r & 7), which keeps the
-// ds_read_b128 operand fetches conflict-free; the swizzle is applied by choosing which global
-// chunk each lane loads.  Per k-tile: four k-steps of MFMAs on fragments read one k-step ahead;
+// of a stage is 8 slots (128 B, half of the 256 bytes the LDS banks span), logical chunk c of
+// row r in slot c ^ ((r >> 1) & 7): sixteen consecutive rows then land on sixteen different
+// 16-byte bank groups, which keeps the ds_read_b128 operand fetches conflict-free (with
+// c ^ (r & 7) rows two apart collide and the bank-conflict counter showed the LDS stalled for
+// half of its active cycles); the swizzle is applied by choosing which global chunk each lane
+// loads.  Per k-tile: four k-steps of MFMAs on fragments read one k-step ahead;
 // after the third, vmcnt(0) + one bare s_barrier say that the next tile has landed for every
 // wave and that every wave has read its last fragment of this tile, so the loads of the tile
 // after next go into this tile's stage under the fourth k-step (first half) and under the next
 // tile's first k-step (second half).  Loads past the last k-tile re-read the last one into a
 // dead stage, which keeps the loop body branch-free.
 typedef __attribute__((address_space(3))) void lds_void_t;
+// slot swizzle of row r (rows of every stage section start at a multiple of 16)
+#define FF1_SWZ(r) (((r) >> 1) & 7)
 
 template <int ACT, bool GATED, int MI, bool PLAIN>
 __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
@@ -238,14 +243,16 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
 
     // loader: lane -> (row of the 8-row region, slot in the row) -> global chunk (un-swizzled).
     // Byte offsets are relative to the tile's first row and fit 32 bits (checked at launch).
-    const int lrow = lane >> 3, lchunk = (lane & 7) ^ lrow;
+    const int lrow = lane >> 3;
     uint32_t xvo[XQ], wvo[WQ];
 #pragma unroll
     for (int q = 0; q < XQ; ++q)
-        xvo[q] = (uint32_t)min((wave * XQ + q) * 8 + lrow, p.M - 1 - m0) * (uint32_t)(p.ldx * 2) + lchunk * 16;
+        xvo[q] = (uint32_t)min((wave * XQ + q) * 8 + lrow, p.M - 1 - m0) * (uint32_t)(p.ldx * 2) +
+                 (uint32_t)(((lane & 7) ^ FF1_SWZ((wave * XQ + q) * 8 + lrow)) * 16);
 #pragma unroll
     for (int q = 0; q < WQ; ++q)
-        wvo[q] = (uint32_t)min((wave * WQ + q) * 8 + lrow, p.F - 1 - n0) * (uint32_t)(p.ldw * 2) + lchunk * 16;
+        wvo[q] = (uint32_t)min((wave * WQ + q) * 8 + lrow, p.F - 1 - n0) * (uint32_t)(p.ldw * 2) +
+                 (uint32_t)(((lane & 7) ^ FF1_SWZ((wave * WQ + q) * 8 + lrow)) * 16);
     // raw buffer descriptors (32-bit data format word of gfx9-family raw buffers); every access is
     // in range by construction, the record count is not relied upon
     constexpr int RSRC_FLAGS = 0x00020000, RSRC_RECORDS = 0x7FFFFFFE;
@@ -300,7 +307,7 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
                 accG[mi][ni][i] = 0.0f;
             }
 
-    const int l31 = lane & 31, lh = lane >> 5, sw = l31 & 7;
+    const int l31 = lane & 31, lh = lane >> 5, sw = FF1_SWZ(l31);
     // byte addresses (inside a stage) of this lane's fragment rows, per k-step
     uint32_t abase[4], bbase[4];
 #pragma unroll
