@@ -98,9 +98,20 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 // PLAIN: the kernel serves as a plain C = A B^T with fp32 output (one range of a split contraction):
 // no activation, no biases, no row sums; Z points at that range's [M][F] slab.
+// One accumulator value out of its AGPR, at the point of use.  Left to itself the compiler copies all
+// 256 accumulator registers into VGPRs at the end of the k loop and spills a hundred of them around
+// the epilogue; the asm operand keeps each value in the accumulation file until it is wanted.
+__device__ __forceinline__ float ff1_acc_read(float a)
+{
+    float v;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+    return v;
+}
+
 template <int ACT, bool GATED, int MI, bool PLAIN>
-__device__ __forceinline__ void ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (&accU)[MI][2], f32x16 (&accG)[MI][2],
-                                                    float (*rs)[64 * MI], uint32_t stage_lds, int m0, int n0, int tile_n)
+__device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (&accU)[MI][2], f32x16 (&accG)[MI][2],
+                                                    float (*rs)[64 * MI], uint32_t rs_lds, uint32_t patch_lds, int m0, int n0,
+                                                    int tile_n)
 {
     constexpr int BM = 64 * MI;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -110,15 +121,15 @@ __device__ __forceinline__ void ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
     const uint16_t *b1p = (const uint16_t *)p.b1, *bgp = (const uint16_t *)p.bg;
     if (vec && !hb) {
         // The usual case (no biases, 16-byte aligned rows of Z, F a multiple of 4).  A wave's
-        // 32-token x 64-neuron block goes through a private LDS patch (rows padded to 272 B, the
-        // stages are dead by now) and leaves as 16-byte stores that cover four whole 256-byte
-        // row pieces per instruction; storing straight from the accumulator layout would touch
-        // 32 different rows with 32 bytes each.
-        constexpr int PR = 272;                                  // padded row, bytes
-        const uint32_t patch = stage_lds + (uint32_t)(wave * 32 * PR);
-        const uint32_t wr = patch + (uint32_t)(l31 * PR + lh * 16);
+        // 32-token x 64-neuron block goes through a private LDS patch (32 rows of 256 B, 16-byte
+        // chunk c of row r at c ^ (r & 15): writes and reads both spread evenly over the banks) and
+        // leaves as 16-byte stores that cover four whole 256-byte row pieces per instruction;
+        // storing straight from the accumulator layout would touch 32 different rows with 32 bytes
+        // each.  Every LDS access here is inline asm: the next tile's first LDS-DMA loads are in
+        // flight, and an access the compiler knows about would wait for them (and for the Z stores).
+        const uint32_t patch = patch_lds + (uint32_t)(wave * 32 * 256);
+        const uint32_t wr = patch + (uint32_t)(l31 * 256);
         const int rrow = lane >> 4, rch = lane & 15;
-        const uint32_t rd = patch + (uint32_t)(rrow * PR + rch * 16);
         const int ncol = n0 + wn * 64 + rch * 4;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
@@ -131,64 +142,91 @@ __device__ __forceinline__ void ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
                     f32x4_t v;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float u = accU[mi][ni][g * 4 + e];
-                        v[e] = PLAIN ? u : (GATED ? act_apply_t<ACT>(accG[mi][ni][g * 4 + e]) * u : act_apply_t<ACT>(u));
+                        const float u = ff1_acc_read(accU[mi][ni][g * 4 + e]);
+                        v[e] = PLAIN ? u : (GATED ? act_apply_t<ACT>(ff1_acc_read(accG[mi][ni][g * 4 + e])) * u : act_apply_t<ACT>(u));
                     }
                     if (n0 + wn * 64 + ni * 32 + g * 8 + lh * 4 >= p.F)
                         v = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
                     sq = fmaf(v[0], v[0], sq); sq = fmaf(v[1], v[1], sq);
                     sq = fmaf(v[2], v[2], sq); sq = fmaf(v[3], v[3], sq);
-                    asm volatile("ds_write_b128 %0, %1" :: "v"(wr + (uint32_t)((ni * 32 + g * 8) * 4)), "v"(v) : "memory");
+                    const int cw = (ni * 8 + g * 2 + lh) ^ (l31 & 15);
+                    asm volatile("ds_write_b128 %0, %1" :: "v"(wr + (uint32_t)(cw * 16)), "v"(v) : "memory");
+                    // keep the groups apart: left alone, the scheduler pulls the accumulator reads of all
+                    // 32 groups to the front and spills a hundred registers
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            rs[wn * 2 + lh][lrow] = sq;
+            if (!PLAIN)
+                asm volatile("ds_write_b32 %0, %1" :: "v"(rs_lds + (uint32_t)(((wn * 2 + lh) * BM + lrow) * 4)), "v"(sq) : "memory");
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             // rows 4j + rrow of the patch, 16 bytes per lane
             const int tok0 = m0 + wm * (32 * MI) + mi * 32 + rrow;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 f32x4_t v;
-                asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(rd + (uint32_t)(j * 4 * PR)) : "memory");
+                const int row = 4 * j + rrow;
+                asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(patch + (uint32_t)(row * 256 + ((rch ^ (row & 15)) * 16))) : "memory");
                 asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v) :: "memory");
                 const int tok = tok0 + 4 * j;
                 if (tok < p.M && ncol < p.F)
                     *(f32x4_t *)(p.Z + (int64_t)tok * p.ldz + ncol) = v;
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-    } else {
+        if (PLAIN)
+            return true;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        for (int r = tid; r < BM; r += G_THREADS) {
+            float q0, q1, q2, q3;
+            const uint32_t ra = rs_lds + (uint32_t)(r * 4);
+            asm volatile("ds_read_b32 %0, %1" : "=v"(q0) : "v"(ra));
+            asm volatile("ds_read_b32 %0, %1" : "=v"(q1) : "v"(ra + (uint32_t)(BM * 4)));
+            asm volatile("ds_read_b32 %0, %1" : "=v"(q2) : "v"(ra + (uint32_t)(2 * BM * 4)));
+            asm volatile("ds_read_b32 %0, %1" : "=v"(q3) : "v"(ra + (uint32_t)(3 * BM * 4)));
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(q0), "+v"(q1), "+v"(q2), "+v"(q3));
+            if (m0 + r < p.M)
+                p.rowpart[(int64_t)(m0 + r) * p.nt + tile_n] = (q0 + q1) + (q2 + q3);
+        }
+        return true;
+    }
+    // biases, or rows of Z that 16-byte stores cannot take: element by element, no LDS patch
+    // (LDS accesses the compiler knows about: they wait for whatever LDS-DMA is in flight)
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-            const int lrow = wm * (32 * MI) + mi * 32 + l31;
-            const bool rowok = m0 + lrow < p.M;
-            float *zrow = p.Z + (int64_t)min(m0 + lrow, p.M - 1) * p.ldz;
-            float sq = 0.0f;
+    for (int mi = 0; mi < MI; ++mi) {
+        const int lrow = wm * (32 * MI) + mi * 32 + l31;
+        const bool rowok = m0 + lrow < p.M;
+        float *zrow = p.Z + (int64_t)min(m0 + lrow, p.M - 1) * p.ldz;
+        float sq = 0.0f;
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
+        for (int ni = 0; ni < 2; ++ni) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int col = n0 + wn * 64 + ni * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
-                    const int cj = min(col, p.F - 1);
-                    float u = accU[mi][ni][i];
-                    float gt = GATED ? accG[mi][ni][i] : 0.0f;
-                    if (!PLAIN && b1p) u += bf16_bits_to_f32(b1p[cj]);
-                    if (!PLAIN && GATED && bgp) gt += bf16_bits_to_f32(bgp[cj]);
-                    const float z = PLAIN ? u : (GATED ? act_apply_t<ACT>(gt) * u : act_apply_t<ACT>(u));
-                    if (col < p.F) {
-                        sq = fmaf(z, z, sq);
-                        if (rowok)
-                            zrow[col] = z;
-                    }
+            for (int i = 0; i < 16; ++i) {
+                const int col = n0 + wn * 64 + ni * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
+                const int cj = min(col, p.F - 1);
+                float u = ff1_acc_read(accU[mi][ni][i]);
+                float gt = GATED ? ff1_acc_read(accG[mi][ni][i]) : 0.0f;
+                if (!PLAIN && b1p) u += bf16_bits_to_f32(b1p[cj]);
+                if (!PLAIN && GATED && bgp) gt += bf16_bits_to_f32(bgp[cj]);
+                const float z = PLAIN ? u : (GATED ? act_apply_t<ACT>(gt) * u : act_apply_t<ACT>(u));
+                if (col < p.F) {
+                    sq = fmaf(z, z, sq);
+                    if (rowok)
+                        zrow[col] = z;
                 }
             }
-            rs[wn * 2 + lh][lrow] = sq;
         }
+        rs[wn * 2 + lh][lrow] = sq;
     }
     if (PLAIN)
-        return;
+        return false;
     __syncthreads();
     for (int r = tid; r < BM; r += G_THREADS)
         if (m0 + r < p.M)
             p.rowpart[(int64_t)(m0 + r) * p.nt + tile_n] = (rs[0][r] + rs[1][r]) + (rs[2][r] + rs[3][r]);
+    return false;
 }
 
 // Main path (d a multiple of 64).  Operand tiles go from global memory straight into LDS
@@ -225,45 +263,55 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
     __shared__ u32x4 lds[2 * STAGE];
     __shared__ float rs[4][BM];
 
-    // XCD-aware tile order; with a split contraction the ranges of one tile are `ntile` ids apart
-    const int ntile = p.mt * p.nt, nblk = ntile * p.splits;
-    const int per_xcd = (nblk + 7) / 8;
-    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (logical >= nblk)
-        return;
-    const int split = logical / ntile, tile = logical % ntile;
-    const int tile_n = tile / p.mt, tile_m = tile % p.mt;
-    const int m0 = tile_m * BM, n0 = tile_n * G_BN;
-    if (PLAIN)
-        p.Z += (int64_t)split * p.M * p.ldz;
-
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
 
-    // loader: lane -> (row of the 8-row region, slot in the row) -> global chunk (un-swizzled).
-    // Byte offsets are relative to the tile's first row and fit 32 bits (checked at launch).
-    const int lrow = lane >> 3;
-    uint32_t xvo[XQ], wvo[WQ];
-#pragma unroll
-    for (int q = 0; q < XQ; ++q)
-        xvo[q] = (uint32_t)min((wave * XQ + q) * 8 + lrow, p.M - 1 - m0) * (uint32_t)(p.ldx * 2) +
-                 (uint32_t)(((lane & 7) ^ FF1_SWZ((wave * XQ + q) * 8 + lrow)) * 16);
-#pragma unroll
-    for (int q = 0; q < WQ; ++q)
-        wvo[q] = (uint32_t)min((wave * WQ + q) * 8 + lrow, p.F - 1 - n0) * (uint32_t)(p.ldw * 2) +
-                 (uint32_t)(((lane & 7) ^ FF1_SWZ((wave * WQ + q) * 8 + lrow)) * 16);
-    // raw buffer descriptors (32-bit data format word of gfx9-family raw buffers); every access is
-    // in range by construction, the record count is not relied upon
+    // XCD-aware tile order (workgroup ids congruent mod 8 share an XCD: each XCD walks its own
+    // contiguous range of tiles, its workgroups side by side); with a split contraction the ranges
+    // of one tile are `ntile` ids apart.  The grid holds one workgroup per CU and every workgroup
+    // walks through its tiles itself, so that the first loads of the next tile can go out before
+    // the epilogue of this one (a workgroup per tile leaves the CU idle while the next one starts).
+    const int ntile = p.mt * p.nt, nblk = ntile * p.splits;
+    const int per_xcd = (nblk + 7) / 8;
+    const int wg_per_xcd = gridDim.x >> 3;
+    int slot = blockIdx.x >> 3;
+    if (slot >= per_xcd || (int)(blockIdx.x & 7) * per_xcd + slot >= nblk)
+        return;
+
+    // per-tile addressing: the loader maps lane -> (row of the 8-row region, slot in the row) ->
+    // global chunk (un-swizzled); byte offsets are relative to the tile's first row and fit 32 bits
+    // (checked at launch).  Raw buffer descriptors (32-bit data format word of gfx9-family raw
+    // buffers); every access is in range by construction, the record count is not relied upon.
     constexpr int RSRC_FLAGS = 0x00020000, RSRC_RECORDS = 0x7FFFFFFE;
-    const __amdgpu_buffer_rsrc_t rX = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)((const uint16_t *)p.X + (int64_t)m0 * p.ldx), 0, RSRC_RECORDS, RSRC_FLAGS);
-    const __amdgpu_buffer_rsrc_t rW1 = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)((const uint16_t *)p.W1 + (int64_t)n0 * p.ldw), 0, RSRC_RECORDS, RSRC_FLAGS);
-    const __amdgpu_buffer_rsrc_t rWg = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)((const uint16_t *)(GATED ? p.Wg : p.W1) + (int64_t)n0 * p.ldw), 0, RSRC_RECORDS, RSRC_FLAGS);
-    const int kt0 = split * p.kt_per_split;
-    const int KT = min(p.kt_per_split, p.d / BK - kt0);      // k-tiles of this range (>= 1 by construction)
+    const int lrow = lane >> 3;
+    int m0, n0, tile_n, kt0, KT;
+    float *Zt;
+    uint32_t xvo[XQ], wvo[WQ];
+    __amdgpu_buffer_rsrc_t rX, rW1, rWg;
+#define FF1_TILE_ADDR(logical_)                                                                          \
+    {                                                                                                    \
+        const int split_ = (logical_) / ntile, tile_ = (logical_) % ntile;                               \
+        tile_n = tile_ / p.mt;                                                                           \
+        m0 = (tile_ % p.mt) * BM;                                                                        \
+        n0 = tile_n * G_BN;                                                                              \
+        Zt = PLAIN ? p.Z + (int64_t)split_ * p.M * p.ldz : p.Z;                                          \
+        _Pragma("unroll") for (int q = 0; q < XQ; ++q)                                                   \
+            xvo[q] = (uint32_t)min((wave * XQ + q) * 8 + lrow, p.M - 1 - m0) * (uint32_t)(p.ldx * 2) +   \
+                     (uint32_t)(((lane & 7) ^ FF1_SWZ((wave * XQ + q) * 8 + lrow)) * 16);                \
+        _Pragma("unroll") for (int q = 0; q < WQ; ++q)                                                   \
+            wvo[q] = (uint32_t)min((wave * WQ + q) * 8 + lrow, p.F - 1 - n0) * (uint32_t)(p.ldw * 2) +   \
+                     (uint32_t)(((lane & 7) ^ FF1_SWZ((wave * WQ + q) * 8 + lrow)) * 16);                \
+        rX = __builtin_amdgcn_make_buffer_rsrc((void *)((const uint16_t *)p.X + (int64_t)m0 * p.ldx), 0, \
+                                               RSRC_RECORDS, RSRC_FLAGS);                                \
+        rW1 = __builtin_amdgcn_make_buffer_rsrc((void *)((const uint16_t *)p.W1 + (int64_t)n0 * p.ldw), 0, \
+                                                RSRC_RECORDS, RSRC_FLAGS);                               \
+        rWg = __builtin_amdgcn_make_buffer_rsrc((void *)((const uint16_t *)(GATED ? p.Wg : p.W1) + (int64_t)n0 * p.ldw), 0, \
+                                                RSRC_RECORDS, RSRC_FLAGS);                               \
+        kt0 = split_ * p.kt_per_split;                                                                   \
+        KT = min(p.kt_per_split, p.d / BK - kt0);      /* k-tiles of this range (>= 1 by construction) */ \
+    }
+    FF1_TILE_ADDR((int)(blockIdx.x & 7) * per_xcd + slot)
 
 // LDS-DMA instruction number q (0 .. NLOADS-1: the X regions, then W1, then Wg) of k-tile kt_.
 // The weight tiles carry the non-temporal hint (each is used by one wave of tiles and then never
@@ -297,15 +345,6 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
 #define FF1_PIN() __builtin_amdgcn_sched_barrier(0)
 
     f32x16 accU[MI][2], accG[MI][2];
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                accU[mi][ni][i] = 0.0f;
-                accG[mi][ni][i] = 0.0f;
-            }
 
     const int l31 = lane & 31, lh = lane >> 5, sw = FF1_SWZ(l31);
     // byte addresses (inside a stage) of this lane's fragment rows, per k-step
@@ -368,40 +407,91 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
         }                                                                                      \
     }
 
-#pragma unroll
-    for (int q = 0; q < NLOADS; ++q)
-        FF1_LOAD_ONE(0, q)
-#pragma unroll
-    for (int q = 0; q < H1; ++q)
-        FF1_LOAD_ONE(1, q)
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(H1));        // tile 0 landed
-    FF1_BARRIER()
+    // k-tile 0 of a tile goes to stage 0 in full; of k-tile 1 the first half of the loads goes out with
+    // it when that leaves the other half of stage 1 (32 KB, the gate/up weights' part) free for the
+    // epilogue's patches of the tile before, i.e. for gated blocks; otherwise it follows the epilogue.
+    constexpr int EARLY1 = GATED ? H1 : 0;
+    // Global store instructions that EVERY wave issues in the epilogue's usual path on a tile that lies
+    // wholly inside the matrix (8 per 32-token block, plus the row sums when all four waves write them).
+    // The wait for k-tile 0 of the next tile may leave that many operations outstanding, no more: a
+    // wave that issued fewer stores than the wait allows would sail through before its loads landed.
+    constexpr int EPI_STORES = MI * 8 + ((!PLAIN && MI == 4) ? 1 : 0);
+    const uint32_t rs_lds = (uint32_t)(uintptr_t)(lds_void_t *)rs;
+    const uint32_t patch_lds = lds0 + (uint32_t)(STAGE * 16) + (GATED ? (uint32_t)(BM * 128) : 0u);
+#define FF1_FIRST_LOADS()                                                                      \
+    {                                                                                          \
+        _Pragma("unroll") for (int q = 0; q < NLOADS; ++q) FF1_LOAD_ONE(0, q)                  \
+        _Pragma("unroll") for (int q = 0; q < EARLY1; ++q) FF1_LOAD_ONE(1, q)                  \
+    }
+    FF1_FIRST_LOADS()
+    bool stores_known = false;         // the tile before was whole and took the epilogue's usual path
     if (!GATED) {
         fg[0][0] = fg[0][1] = fg[1][0] = fg[1][1] = (u32x4){0u, 0u, 0u, 0u};
     }
-    {
-        const uint32_t sa = lds0 + abase[0], sb = lds0 + bbase[0];
+    for (;;) {
 #pragma unroll
-        for (int r = 0; r < NREADS; ++r)
-            FF1_READ_ONE(0, r, sa, sb)
+        for (int q = EARLY1; q < H1; ++q)
+            FF1_LOAD_ONE(1, q)
+        // k-tile 0 has landed when only the first half of k-tile 1 and (from the second tile on) the
+        // epilogue's stores, all issued after it, are still outstanding
+        if (stores_known)
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(H1 + EPI_STORES));
+        else
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(H1));
+        FF1_BARRIER()
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    accU[mi][ni][i] = 0.0f;
+                    accG[mi][ni][i] = 0.0f;
+                }
+        {
+            const uint32_t sa = lds0 + abase[0], sb = lds0 + bbase[0];
+#pragma unroll
+            for (int r = 0; r < NREADS; ++r)
+                FF1_READ_ONE(0, r, sa, sb)
+        }
+        for (int kt = 0; kt < KT; ++kt) {
+            const uint32_t st_cur = lds0 + (uint32_t)((kt & 1) * STAGE * 16);
+            const uint32_t st_nxt = lds0 + (uint32_t)(((kt + 1) & 1) * STAGE * 16);
+            FF1_WAIT_FRAGS(0)
+            FF1_KSTEP(0, 1, st_cur, 1, kt + 1, H1, NLOADS)     // second half of the next tile's loads
+            FF1_WAIT_FRAGS(1)
+            FF1_KSTEP(1, 0, st_cur, 2, 0, 0, 0)
+            FF1_WAIT_FRAGS(0)
+            FF1_KSTEP(0, 1, st_cur, 3, 0, 0, 0)
+            FF1_WAIT_FRAGS(1)
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));          // tile kt+1 has landed (this wave's part)
+            FF1_BARRIER()                                      // ... every wave's part; tile kt is read out
+            FF1_KSTEP(1, 0, st_nxt, 0, kt + 2, 0, H1)          // first half of the loads of the tile after next
+        }
+        FF1_WAIT_FRAGS(0)                                 // the reads issued for the tile past the end
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));         // no LDS-DMA of this tile is left in flight
+        FF1_BARRIER()
+
+        // this tile's coordinates for the epilogue; then the next tile's first loads go out
+        Ff1Params pt = p;
+        pt.Z = Zt;
+        const int m0c = m0, n0c = n0, tile_nc = tile_n;
+        const bool whole = m0 + BM <= p.M && n0 + G_BN <= p.F;
+        slot += wg_per_xcd;
+        const int logical_n = (int)(blockIdx.x & 7) * per_xcd + slot;
+        const bool more = slot < per_xcd && logical_n < nblk;
+        if (more) {
+            FF1_TILE_ADDR(logical_n)
+            FF1_FIRST_LOADS()
+        }
+        const bool usual = ff1_mfma_epilogue_t<ACT, GATED, MI, PLAIN>(pt, accU, accG, rs, rs_lds, patch_lds, m0c, n0c, tile_nc);
+        if (!more)
+            break;
+        FF1_BARRIER()              // every wave is done with its patch and the row sums
+        stores_known = usual && whole;
     }
-    for (int kt = 0; kt < KT; ++kt) {
-        const uint32_t st_cur = lds0 + (uint32_t)((kt & 1) * STAGE * 16);
-        const uint32_t st_nxt = lds0 + (uint32_t)(((kt + 1) & 1) * STAGE * 16);
-        FF1_WAIT_FRAGS(0)
-        FF1_KSTEP(0, 1, st_cur, 1, kt + 1, H1, NLOADS)     // second half of the next tile's loads
-        FF1_WAIT_FRAGS(1)
-        FF1_KSTEP(1, 0, st_cur, 2, 0, 0, 0)
-        FF1_WAIT_FRAGS(0)
-        FF1_KSTEP(0, 1, st_cur, 3, 0, 0, 0)
-        FF1_WAIT_FRAGS(1)
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));          // tile kt+1 has landed (this wave's part)
-        FF1_BARRIER()                                      // ... every wave's part; tile kt is read out
-        FF1_KSTEP(1, 0, st_nxt, 0, kt + 2, 0, H1)          // first half of the loads of the tile after next
-    }
-    FF1_WAIT_FRAGS(0)                                 // the reads issued for the tile past the end
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));         // no LDS-DMA may outlive the loop
-    FF1_BARRIER()
+#undef FF1_TILE_ADDR
+#undef FF1_FIRST_LOADS
 #undef FF1_LOAD_ONE
 #undef FF1_BARRIER
 #undef FF1_DS_READ
@@ -410,8 +500,6 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
 #undef FF1_MFMA_ONE
 #undef FF1_WAIT_FRAGS
 #undef FF1_KSTEP
-
-    ff1_mfma_epilogue_t<ACT, GATED, MI, PLAIN>(p, accU, accG, rs, lds0, m0, n0, tile_n);
 #endif
 }
 
@@ -653,18 +741,33 @@ int ff1_ntiles(const griffin_layer &L)
     return (L.n + bn - 1) / bn;
 }
 
+// one workgroup per CU (a multiple of 8, so that every XCD gets the same number), fewer if there are fewer tiles
+static int ff1_grid(int nblk)
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8)
+            n = 256;
+        cus = n & ~7;
+    }
+    const int want = ((nblk + 7) / 8) * 8;
+    return want < cus ? want : cus;
+}
+
 template <int ACT, int MI>
 static void launch_mfma(const Ff1Params &p, bool gated, hipStream_t st)
 {
     const int nblk = p.mt * p.nt;
-    dim3 grid(((nblk + 7) / 8) * 8), block(G_THREADS);
+    dim3 grid(ff1_grid(nblk)), block(G_THREADS);
+    dim3 grid_all(((nblk + 7) / 8) * 8);           // the register-staged kernel takes one tile per workgroup
     // the direct-to-LDS kernel wants whole 64-element k-tiles and 32-bit byte offsets inside a tile
     const bool ktail = p.d % 64 != 0 || p.ldx > (1 << 21) || p.ldw > (1 << 21);
     if (gated) {
-        if (ktail) hipLaunchKernelGGL((ff1_bf16_mfma_staged_kernel<ACT, true, MI, true>), grid, block, 0, st, p);
+        if (ktail) hipLaunchKernelGGL((ff1_bf16_mfma_staged_kernel<ACT, true, MI, true>), grid_all, block, 0, st, p);
         else hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, true, MI, false>), grid, block, 0, st, p);
     } else {
-        if (ktail) hipLaunchKernelGGL((ff1_bf16_mfma_staged_kernel<ACT, false, MI, true>), grid, block, 0, st, p);
+        if (ktail) hipLaunchKernelGGL((ff1_bf16_mfma_staged_kernel<ACT, false, MI, true>), grid_all, block, 0, st, p);
         else hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, false, MI, false>), grid, block, 0, st, p);
     }
 }
@@ -759,11 +862,11 @@ int launch_gemm_nt_partials(const void *A, int64_t lda, const void *B, int64_t l
     if (M > 128) {
         p.mt = (int32_t)((M + 255) / 256);
         const int nblk = p.mt * p.nt * splits;
-        hipLaunchKernelGGL((ff1_bf16_mfma_kernel<GRIFFIN_ACT_RELU, false, 4, true>), dim3(((nblk + 7) / 8) * 8), dim3(G_THREADS), 0, st, p);
+        hipLaunchKernelGGL((ff1_bf16_mfma_kernel<GRIFFIN_ACT_RELU, false, 4, true>), dim3(ff1_grid(nblk)), dim3(G_THREADS), 0, st, p);
     } else {
         p.mt = (int32_t)((M + 127) / 128);
         const int nblk = p.mt * p.nt * splits;
-        hipLaunchKernelGGL((ff1_bf16_mfma_kernel<GRIFFIN_ACT_RELU, false, 2, true>), dim3(((nblk + 7) / 8) * 8), dim3(G_THREADS), 0, st, p);
+        hipLaunchKernelGGL((ff1_bf16_mfma_kernel<GRIFFIN_ACT_RELU, false, 2, true>), dim3(ff1_grid(nblk)), dim3(G_THREADS), 0, st, p);
     }
     return check_launch("ff1_bf16_mfma_kernel");
 }
