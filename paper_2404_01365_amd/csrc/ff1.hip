@@ -504,7 +504,7 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
 }
 
 // ------------------------------------------------------------------------------------ bf16 / MFMA, register-staged
-// Fallback for d not a multiple of 32 (the k tail is zero-filled in registers, which the
+// Fallback for d not a multiple of 64 or row strides too long for 32-bit byte offsets (the k tail is zero-filled in registers, which the
 // direct-to-LDS loads cannot do): 16-byte global loads staged through VGPRs into two LDS
 // buffers of BK = 64.
 template <int ACT, bool GATED, int MI, bool KTAIL>
