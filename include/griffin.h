@@ -190,8 +190,12 @@ int griffin_ff_decode_multi(const griffin_layer *Cs, int32_t batch, const void *
                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * The same without compact copies: row b uses neurons idx[b][0..k-1] of the full block L,
- * read in place.  idx [batch][k] int32 device (out-of-range entries are clamped).
+ * The same without compact copies: row b uses neurons idx[b][0..k-1] (distinct) of the full block
+ * L, read in place.  idx [batch][k] int32 device (out-of-range entries are clamped).
+ * With a workspace of griffin_decode_workspace_bytes(d, L->n, batch) bytes (sized for the whole
+ * block rather than for k neurons) five rows and more take ONE pass over the whole block, every row
+ * dropping the neurons outside its own set: the sets of a batch cover most of the block between them,
+ * so this moves far fewer bytes than a pass per row (bf16, d a multiple of 512 up to 5120).
  */
 int griffin_ff_decode_indexed(const griffin_layer *L, const int32_t *idx, int32_t k,
                               int32_t batch, const void *x, void *y, void *workspace,

@@ -301,7 +301,8 @@ size_t griffin_decode_workspace_bytes(int32_t d, int32_t n, int32_t batch)
         return 0;
     size_t floats = (size_t)decode_parts(n, batch) * batch * d;
     if (batch >= DEC_BATCH_MIN_ROWS && decode_batch_supported(d, n, true)) {
-        const size_t fb = decode_batch_workspace_floats(d, n, batch);
+        // also enough for the masked pass of griffin_ff_decode_indexed over a block of n neurons
+        const size_t fb = decode_masked_workspace_floats(d, n, batch);
         if (fb > floats)
             floats = fb;
     }

@@ -158,7 +158,9 @@ int launch_decode_split(const DecodeJob &job, hipStream_t st, hipEvent_t ev_mid)
 // rows 5.. of a batch through one shared block: matrix-core path (decode_batch.hip)
 bool decode_batch_supported(int32_t d, int32_t n, bool bf16);
 size_t decode_batch_workspace_floats(int32_t d, int32_t n, int32_t batch);
-int launch_decode_batch_front(const DecodeJob &job, int *NR_out, hipStream_t st);
+size_t decode_masked_workspace_floats(int32_t d, int32_t n_src, int32_t batch);
+int launch_decode_batch_front(const DecodeJob &job, int32_t n_block, const int32_t *idx, int32_t k, int *NR_out,
+                              hipStream_t st);
 constexpr int DEC_BATCH_MIN_ROWS = 5;
 int decode_parts(int32_t n, int32_t batch);
 void set_decode_probe(hipEvent_t begin, hipEvent_t mid, hipEvent_t end);

@@ -352,7 +352,13 @@ int launch_decode(const DecodeJob &job, hipStream_t st)
     // five rows and more through one shared block: the matrix-core path
     const bool batch_path = !job.multi && !job.idx && job.batch >= DEC_BATCH_MIN_ROWS &&
                             decode_batch_supported(job.d, job.n, job.bf16);
-    if (job.part_bytes < (batch_path ? decode_batch_workspace_floats(job.d, job.n, job.batch)
+    // five rows and more with their own sets inside one block: one masked pass over the whole block, if
+    // the caller's workspace was sized for the whole block (else row by row through the index lists)
+    const bool masked_path = !job.multi && job.idx && job.batch >= DEC_BATCH_MIN_ROWS && job.W2 &&
+                             decode_batch_supported(job.d, job.n_src, job.bf16) &&
+                             job.part_bytes >= decode_masked_workspace_floats(job.d, job.n_src, job.batch) * sizeof(float);
+    if (!masked_path &&
+        job.part_bytes < (batch_path ? decode_batch_workspace_floats(job.d, job.n, job.batch)
                                      : (size_t)P * job.batch * job.d) * sizeof(float))
         return GRIFFIN_EWORKSPACE;
 
@@ -395,8 +401,9 @@ int launch_decode(const DecodeJob &job, hipStream_t st)
     }
     if (!job.W2 && !job.multi)
         return GRIFFIN_EUNSUPPORTED;       // only the transposed copy is there and this call cannot use it
-    if (batch_path) {
-        int rc = launch_decode_batch_front(job, &P, st);
+    if (batch_path || masked_path) {
+        int rc = masked_path ? launch_decode_batch_front(job, job.n_src, job.idx, job.n, &P, st)
+                             : launch_decode_batch_front(job, job.n, nullptr, 0, &P, st);
         if (rc != GRIFFIN_OK)
             return rc;
         if (ev_mid && hipEventRecord(ev_mid, st) != hipSuccess)

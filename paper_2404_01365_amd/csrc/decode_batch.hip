@@ -52,6 +52,7 @@ struct BatchParams {
     int32_t P;               // workgroups of the first kernel
     int32_t NR, CS;          // neuron ranges x column slices of the second kernel
     int32_t TB;              // groups between two meetings of the first kernel's waves
+    const uint32_t *mask;    // per neuron, bit b set if row b of this pass uses the neuron; NULL: every row uses all
 };
 
 // cache policy of the weight stream: read once, so non-temporal (135 MB in a bare LDS-DMA read
@@ -221,7 +222,9 @@ __global__ __launch_bounds__(MAXT) void ff_batch_gu_kernel(BatchParams p)
                 const int j = min(G * ((int)blockIdx.x + (t_first + ti) * p.P) + jj, p.n - 1);
                 if (p.b1) u += bf16_bits_to_f32(((const uint16_t *)p.b1)[j]);
                 if (GATED && p.bg) g += bf16_bits_to_f32(((const uint16_t *)p.bg)[j]);
-                const float zv = GATED ? act_apply(p.act, g) * u : act_apply(p.act, u);
+                float zv = GATED ? act_apply(p.act, g) * u : act_apply(p.act, u);
+                if (p.mask && !((p.mask[j] >> b) & 1u))
+                    zv = 0.0f;                 // this row's own expert set does not hold the neuron
                 asm volatile("ds_write_b32 %0, %1" :: "v"(ztab_a + (uint32_t)((((t_first + ti) * G + jj) * 16 + b) * 4)), "v"(zv) : "memory");
             }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -351,6 +354,28 @@ __global__ __launch_bounds__(BT_WAVES2 * 64) void ff_batch_down_kernel(BatchPara
         }
 }
 
+// Rows with their own expert sets through the FULL block in one pass (Section 4.2: every sample picks
+// its own neurons): the sets of a batch cover nearly every neuron between them (16 half-sets of a
+// 14336-neuron block: all of it), so streaming the block once and dropping, per row, the neurons its
+// set does not hold moves 8 times fewer bytes than streaming 16 compact blocks.  mask[j] collects,
+// for 16 rows, which of them selected neuron j.
+__global__ __launch_bounds__(256) void batch_mask_zero_kernel(uint32_t *mask, int n)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j < n)
+        mask[j] = 0u;
+}
+
+__global__ __launch_bounds__(256) void batch_mask_build_kernel(const int32_t *idx, int rows, int k, int n_src, uint32_t *mask)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y;
+    if (t >= k || b >= rows)
+        return;
+    int j = idx[(int64_t)b * k + t];
+    j = j < 0 ? 0 : (j >= n_src ? n_src - 1 : j);
+    atomicOr(&mask[j], 1u << b);
+}
+
 // Can the batch path take this shape?  d in whole 512-element slices, at most 10 of them (one
 // wave each, 168 registers per lane), and few enough neuron groups per workgroup for the LDS
 // table of Z.
@@ -379,11 +404,19 @@ size_t decode_batch_workspace_floats(int32_t d, int32_t n, int32_t batch)
     return (size_t)batch * decode_batch_ranges(d, n) * d + (size_t)n * 16 + 64;
 }
 
+// floats of workspace of the masked pass: the batch pass over the full block plus one mask word per neuron
+size_t decode_masked_workspace_floats(int32_t d, int32_t n_src, int32_t batch)
+{
+    return decode_batch_workspace_floats(d, n_src, batch) + (size_t)n_src + 64;
+}
+
 // Runs both kernels for every group of up to 16 rows; leaves part[b][NR][d] for the reduce kernel.
-int launch_decode_batch_front(const DecodeJob &job, int *NR_out, hipStream_t st)
+// n_block neurons in the block; idx (or NULL) [batch][k]: the rows' own sets inside that block.
+int launch_decode_batch_front(const DecodeJob &job, int32_t n_block, const int32_t *idx, int32_t k, int *NR_out,
+                              hipStream_t st)
 {
     const int R = job.d / 512;
-    const int NR = decode_batch_ranges(job.d, job.n), CS = job.d / BT_COLS;
+    const int NR = decode_batch_ranges(job.d, n_block), CS = job.d / BT_COLS;
     *NR_out = NR;
     const bool gated = job.Wg != nullptr;
     const int NMAT = gated ? 2 : 1, UNIT = BT_G * NMAT * 1024;
@@ -391,7 +424,7 @@ int launch_decode_batch_front(const DecodeJob &job, int *NR_out, hipStream_t st)
     if (NSTG > 4) NSTG = 4;
     if (NSTG < 2)
         return GRIFFIN_EUNSUPPORTED;
-    const int npairs = (job.n + BT_G - 1) / BT_G;
+    const int npairs = (n_block + BT_G - 1) / BT_G;
     const int P1 = npairs < BT_MAX_WG ? npairs : BT_MAX_WG;
     const int Tmax = (npairs + P1 - 1) / P1;
     // room for the waves' partial tiles: all of a workgroup's groups if a ring of two slots or more
@@ -410,16 +443,26 @@ int launch_decode_batch_front(const DecodeJob &job, int *NR_out, hipStream_t st)
 
     BatchParams p;
     p.Wg = job.Wg; p.W1 = job.W1; p.W2 = job.W2; p.bg = job.bg; p.b1 = job.b1;
-    p.ld = job.ld; p.d = job.d; p.n = job.n; p.act = job.act;
+    p.ld = job.ld; p.d = job.d; p.n = n_block; p.act = job.act;
     p.P = P1;
     p.NR = NR; p.CS = CS; p.TB = TB;
     size_t zoff = ((size_t)job.batch * NR * job.d + 63) & ~(size_t)63;
     p.z = job.part + zoff;
+    uint32_t *mask = idx ? (uint32_t *)(p.z + (((size_t)n_block * 16 + 63) & ~(size_t)63)) : nullptr;
+    p.mask = mask;
 
     for (int r0 = 0; r0 < job.batch; r0 += BT_ROWS) {
         p.rows = job.batch - r0 < BT_ROWS ? job.batch - r0 : BT_ROWS;
         p.x = (const uint16_t *)job.x + (int64_t)r0 * job.d;
         p.part = job.part + (size_t)r0 * NR * job.d;
+        if (idx) {
+            hipLaunchKernelGGL(batch_mask_zero_kernel, dim3((n_block + 255) / 256), dim3(256), 0, st, mask, n_block);
+            hipLaunchKernelGGL(batch_mask_build_kernel, dim3((k + 255) / 256, p.rows), dim3(256), 0, st,
+                               idx + (int64_t)r0 * k, p.rows, k, n_block, mask);
+            int rcm = check_launch("batch_mask_build_kernel");
+            if (rcm != GRIFFIN_OK)
+                return rcm;
+        }
         dim3 g1(p.P), b1(R * 64);
 #define BT_GO2(GA, NS, MT)                                                                                     \
         {                                                                                                      \

@@ -82,7 +82,9 @@ def check_layer(cfg, rec, decode_variants=("compact",)):
             Cs.append(C); keep.append(ct)
         # decode through the compact blocks, one token at a time as in generation
         steps = len(rec["seqs"][0]["k"][str(k)]["decode"])
-        wsd = workspace(G.griffin_decode_workspace_bytes(cfg.d, k, max(n_seqs, 1)))
+        # sized for the whole block: with several sequences the index lists then take one masked pass over it
+        wsd = workspace(max(G.griffin_decode_workspace_bytes(cfg.d, k, max(n_seqs, 1)),
+                            G.griffin_decode_workspace_bytes(cfg.d, cfg.d_ff, max(n_seqs, 1))))
         for step in range(steps):
             ys = {}
             y1 = torch.empty((n_seqs, cfg.d), dtype=xt[0].dtype, device="cuda")

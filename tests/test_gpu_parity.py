@@ -508,4 +508,11 @@ def test_decode_takes_the_maximum_batch():
         ref = oracle.ff_decode(c["xt"][b], c["Wg"][idx[b]], c["W1"][idx[b]], c["W2"][idx[b]], synth.ACT_SILU)
         assert max_rel(y_idx[b], ref) <= TOL_OUT[dtype] and max_rel(y_multi[b], ref) <= TOL_OUT[dtype]
         assert max_rel(y_full[b], oracle.ff_decode(c["xt"][b], c["Wg"], c["W1"], c["W2"], synth.ACT_SILU)) <= TOL_OUT[dtype]
-    assert np.array_equal(y_idx, y_multi)
+    # with a workspace sized for the whole block the index lists take one masked pass over the block
+    # (other order of summation than row by row): equal up to bf16 rounding of the output
+    assert np.max(np.abs(y_idx - y_multi)) <= 2.0 ** -6 * np.max(np.abs(y_multi))
+    # with a workspace sized for k neurons they go row by row: the same arithmetic as the compact blocks
+    y4 = torch.empty_like(x)
+    G.griffin_ff_decode_indexed(L, idx_dev, k, B, x, y4, workspace=workspace(G.griffin_decode_workspace_bytes(d, k, B)))
+    sync()
+    assert np.array_equal(to_host(y4), y_multi)
