@@ -516,3 +516,29 @@ def test_decode_takes_the_maximum_batch():
     G.griffin_ff_decode_indexed(L, idx_dev, k, B, x, y4, workspace=workspace(G.griffin_decode_workspace_bytes(d, k, B)))
     sync()
     assert np.array_equal(to_host(y4), y_multi)
+
+
+@pytest.mark.parametrize("d,n,k,B,gated,bias", [
+    (1024, 300, 100, 7, False, True),      # Eq. 2 block with biases, 7 of 16 rows
+    (2048, 999, 500, 19, True, True),      # two groups of rows (16 + 3), odd block size
+    (512, 64, 64, 5, True, False),         # every row keeps the whole block
+])
+def test_indexed_decode_masked_pass_matches_oracle(d, n, k, B, gated, bias):
+    """Rows with their own sets inside one block, one masked pass over the block (workspace sized for it)."""
+    dtype, act = synth.DT_BF16, synth.ACT_GELU_TANH
+    c = synth.small_case(d + n + B, d, n, 4, dtype, T=B, with_bias=bias)
+    Wg = c["Wg"] if gated else None
+    bg = c.get("bg") if gated else None
+    L, _ = dev_layer(Wg, c["W1"], c["W2"], act, dtype, bg, c.get("b1"), c.get("b2"))
+    rng = np.random.default_rng(B)
+    idx = np.stack([np.sort(rng.choice(n, k, replace=False)) for _ in range(B)]).astype(np.int32)
+    x = to_dev(c["xt"], dtype)
+    y = torch.empty_like(x)
+    G.griffin_ff_decode_indexed(L, torch.from_numpy(idx).cuda(), k, B, x, y,
+                                workspace=workspace(G.griffin_decode_workspace_bytes(d, n, B)))
+    sync()
+    got = to_host(y)
+    sub = lambda a, b: None if a is None else a[idx[b]]
+    for b in range(B):
+        ref = oracle.ff_decode(c["xt"][b], sub(Wg, b), c["W1"][idx[b]], c["W2"][idx[b]], act, sub(bg, b), sub(c.get("b1"), b), c.get("b2"))
+        assert max_rel(got[b], ref) <= TOL_OUT[dtype], b
