@@ -261,11 +261,14 @@ __global__ __launch_bounds__(MAXT) void ff_batch_gu_kernel(BatchParams p)
 // No wave waits for another after the first barrier.
 constexpr int BD_ZLD = 520;              // elements per row of the Z tables in LDS
 constexpr int BD_RANGE = 480;            // neurons per workgroup before rounding to multiples of 8
-constexpr int BD_DEPTH = 3;              // ring slots (32 rows x 128 B = 4 KB each) per wave
+constexpr int BD_DEPTH = 3;              // ring slots per wave
+constexpr int BD_REGION = 66;            // 16-byte units per 8-row region: 1 KB of rows + 32 B, so that the four
+                                         // regions a gather touches (rows 8q + i) start on different LDS banks
+constexpr int BD_SLOT = 4 * BD_REGION;   // a slot: 32 rows x 128 B in four regions
 
 __global__ __launch_bounds__(BT_WAVES2 * 64) void ff_batch_down_kernel(BatchParams p, const float *__restrict__ z)
 {
-    __shared__ u32x4_b ring_s[BT_WAVES2 * BD_DEPTH * 256];          // 96 KB
+    __shared__ u32x4_b ring_s[BT_WAVES2 * BD_DEPTH * BD_SLOT];      // 99 KB
     __shared__ uint16_t zhi[16 * BD_ZLD], zlo[16 * BD_ZLD];         // 2 x 16.25 KB
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -288,7 +291,7 @@ __global__ __launch_bounds__(BT_WAVES2 * 64) void ff_batch_down_kernel(BatchPara
 
     const int bq = lane & 15, q = lane >> 4;
     const int c0 = cs * BT_COLS + wave * 64;
-    u32x4_b *ring = ring_s + wave * (BD_DEPTH * 256);
+    u32x4_b *ring = ring_s + wave * (BD_DEPTH * BD_SLOT);
     const uint32_t ring_a = (uint32_t)(uintptr_t)(lds_void_b *)ring;
     const uint32_t za = (uint32_t)(uintptr_t)(lds_void_b *)zhi + (uint32_t)((bq * BD_ZLD + q * 8) * 2);
     const uint32_t zb = (uint32_t)(uintptr_t)(lds_void_b *)zlo + (uint32_t)((bq * BD_ZLD + q * 8) * 2);
@@ -300,7 +303,7 @@ __global__ __launch_bounds__(BT_WAVES2 * 64) void ff_batch_down_kernel(BatchPara
     {                                                                                                        \
         const int row_ = min(j_lo + min((s_), S - 1) * 32 + u * 8 + lrow, p.n - 1);                          \
         __builtin_amdgcn_global_load_lds((gbl_cvoid_b *)(w2 + (int64_t)row_ * p.ld),                         \
-                                         (lds_void_b *)(ring + ((s_) % BD_DEPTH) * 256 + u * 64), 16, 0, BT_NT); \
+                                         (lds_void_b *)(ring + ((s_) % BD_DEPTH) * BD_SLOT + u * BD_REGION), 16, 0, BT_NT); \
     }
     f32x4_b acc[4];
 #pragma unroll
@@ -311,11 +314,11 @@ __global__ __launch_bounds__(BT_WAVES2 * 64) void ff_batch_down_kernel(BatchPara
     for (int s = 0; s < BD_DEPTH - 1; ++s)
         BD_ISSUE(s)
     // LDS reads by inline asm: reads the compiler knows about would wait for every LDS-DMA in flight
-    const uint32_t gat = (uint32_t)(q * 8 * 128 + bq * 2);     // row 8q of the slot, column bq of tile 0
+    const uint32_t gat = (uint32_t)(q * BD_REGION * 16 + bq * 2);   // row 8q of the slot (region q), column bq of tile 0
     for (int s = 0; s < S; ++s) {
         BD_ISSUE(s + BD_DEPTH - 1)
         __builtin_amdgcn_s_waitcnt(bt_vmcnt((BD_DEPTH - 1) * 4));   // the pieces of step s have landed
-        const uint32_t slot = ring_a + (uint32_t)((s % BD_DEPTH) * 4096) + gat;
+        const uint32_t slot = ring_a + (uint32_t)((s % BD_DEPTH) * BD_SLOT * 16) + gat;
         u32x4_b ah, al;
         asm volatile("ds_read_b128 %0, %1" : "=v"(ah) : "v"(za + (uint32_t)(s * 64)));
         asm volatile("ds_read_b128 %0, %1" : "=v"(al) : "v"(zb + (uint32_t)(s * 64)));
