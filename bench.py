@@ -352,7 +352,7 @@ def main():
             traffic = json.load(fh).get("config%d_k%d%s" % (cfg.cid, k, "_gu" if transposed else ""))
 
     out = {
-        "metric": "pruned-FF decode tokens/s + achieved HBM GB/s; select us/layer (prefill)",
+        "metric": "pruned-FF decode tokens/s + achieved HBM GB/s; select \u00b5s/layer (prefill)",
         "value": args.steps * T / wall,
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
