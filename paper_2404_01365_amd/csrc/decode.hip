@@ -47,6 +47,7 @@ struct MultiPtrs {
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 // by value on purpose: bit-casting a vector element expression (v.y) in place picks element 0
 __device__ __forceinline__ bf16x2 as_bf16x2(uint32_t v) { return __builtin_bit_cast(bf16x2, v); }
@@ -245,8 +246,10 @@ __device__ __forceinline__ void decode_body(const DecodeParams &p, const void *W
         if (team == 0 && valid && b + nb < p.batch) {
             float *out = p.part + ((int64_t)(b + nb) * p.P + blockIdx.x) * d + c * E;
 #pragma unroll
-            for (int e = 0; e < E; e += 4)
-                *(float4 *)(out + e) = make_float4(ya[nb][e], ya[nb][e + 1], ya[nb][e + 2], ya[nb][e + 3]);
+            for (int e = 0; e < E; e += 4) {
+                const f32x4 v = {ya[nb][e], ya[nb][e + 1], ya[nb][e + 2], ya[nb][e + 3]};
+                __builtin_nontemporal_store(v, (f32x4 *)(out + e));
+            }
         }
     }
 }

@@ -25,6 +25,7 @@
 //    (NR rows per batch row).  Details at the kernel.
 // The partial rows are then added in a fixed order by the reduce kernel of the single-row path.
 #include "common.h"
+#include <atomic>
 
 namespace griffin {
 
@@ -454,6 +455,10 @@ int launch_decode_batch_front(const DecodeJob &job, int32_t n_block, const int32
     uint32_t *mask = idx ? (uint32_t *)(p.z + (((size_t)n_block * 16 + 63) & ~(size_t)63)) : nullptr;
     p.mask = mask;
 
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess)
+        return set_hip_error(hipGetLastError(), "hipGetDevice");
+    const uint64_t dev_bit = 1ull << (dev & 63);
     for (int r0 = 0; r0 < job.batch; r0 += BT_ROWS) {
         p.rows = job.batch - r0 < BT_ROWS ? job.batch - r0 : BT_ROWS;
         p.x = (const uint16_t *)job.x + (int64_t)r0 * job.d;
@@ -469,12 +474,13 @@ int launch_decode_batch_front(const DecodeJob &job, int32_t n_block, const int32
         dim3 g1(p.P), b1(R * 64);
 #define BT_GO2(GA, NS, MT)                                                                                     \
         {                                                                                                      \
-            static bool attr_set_ = false;     /* raising the dynamic LDS limit is needed once per kernel */   \
-            if (!attr_set_) {                                                                                  \
+            /* raising the dynamic LDS limit is needed once per kernel and device */                           \
+            static std::atomic<uint64_t> attr_set_{0};                                                         \
+            if (!(attr_set_.load(std::memory_order_acquire) & dev_bit)) {                                      \
                 if (hipFuncSetAttribute((const void *)ff_batch_gu_kernel<GA, NS, BT_G, MT>,                    \
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) \
                     return set_hip_error(hipGetLastError(), "hipFuncSetAttribute");                            \
-                attr_set_ = true;                                                                              \
+                attr_set_.fetch_or(dev_bit, std::memory_order_release);                                        \
             }                                                                                                  \
             hipLaunchKernelGGL((ff_batch_gu_kernel<GA, NS, BT_G, MT>), g1, b1, lds, st, p);                    \
         }

@@ -153,6 +153,28 @@ def test_decode_through_transposed_w2_matches_oracle(d, n, k, gated, bias, mode,
             assert max_rel(gotb[b], ref) <= TOL_OUT[dtype]
 
 
+def test_decode_through_transposed_w2_reuses_a_workspace_with_anything_in_it():
+    """The workspace (z between the two streams) may hold anything at first use, and the same workspace
+    serves call after call on one stream with no synchronisation in between (Eq. 4-5, one row)."""
+    dtype, act, d, n, k = synth.DT_BF16, synth.ACT_SILU, 2048, 900, 450
+    c = synth.small_case(77, d, n, 4, dtype, T=6)
+    L, t = dev_layer(c["Wg"], c["W1"], c["W2"], act, dtype)
+    idx_h = np.sort(np.random.default_rng(8).choice(n, k, replace=False)).astype(np.int32)
+    C, ct = empty_compact(L, k, t, interleaved=True, transposed="only")
+    G.griffin_compact(L, torch.from_numpy(idx_h).cuda(), k, C)
+    nbytes = G.griffin_decode_workspace_bytes(C.d, C.n, 1)
+    for fill in (0xFF, 0x00, 0x5A):
+        ws = workspace(nbytes)
+        ws.view(torch.uint8).fill_(fill)
+        ys = [torch.empty(d, dtype=torch.bfloat16, device="cuda") for _ in range(6)]
+        for step in range(6):           # back to back on one stream, no synchronisation in between
+            G.griffin_ff_decode(C, to_dev(c["xt"][step], dtype), ys[step], 1, workspace=ws)
+        sync()
+        for step in range(6):
+            ref = oracle.ff_decode(c["xt"][step], c["Wg"][idx_h], c["W1"][idx_h], c["W2"][idx_h], act)
+            assert max_rel(to_host(ys[step]), ref) <= TOL_OUT[dtype], (fill, step)
+
+
 # ------------------------------------------------------------------ compaction
 @pytest.mark.parametrize("interleaved", [False, True])
 @pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
