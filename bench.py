@@ -316,6 +316,21 @@ def main():
                                           "GBps_weights_once": (3 * k * d * w + 2 * Bsh * d * w) / (b_us * 1e-6) / 1e9},
         }
 
+    # the box's own copy bandwidth, for scale: a plain device-to-device copy of 1 GiB (read + write
+    # counted), larger than the 256 MB Infinity Cache
+    cp_src = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda")
+    cp_dst = torch.empty_like(cp_src)
+    cp_src.zero_()
+    cp_ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for rep in range(6):
+        if rep == 1:
+            cp_ev[0].record()
+        cp_dst.copy_(cp_src)
+    cp_ev[1].record()
+    torch.cuda.synchronize()
+    copy_gbs = 2.0 * (1 << 30) / (cp_ev[0].elapsed_time(cp_ev[1]) * 1e-3 / 5) / 1e9
+    del cp_src, cp_dst
+
     ms_per_step = wall * 1e3 / args.steps
     sel_ms = sum(e[0].elapsed_time(e[1]) for e in stage_ev) / len(stage_ev)
     dec_ms = sum(e[1].elapsed_time(e[2]) for e in stage_ev) / len(stage_ev)
@@ -375,6 +390,7 @@ def main():
             "avg_kernel_us": avg_us, "median_kernel_us": kern_us[len(kern_us) // 2], "launches_timed": len(kern_us),
             "raw_event_span_us": sum(raw_us) / len(raw_us), "event_cost_us": event_overhead_us,
             "unprobed_us_per_layer_token": u,
+            "measured_copy_GBps": copy_gbs, "frac_of_measured_copy": achieved / copy_gbs,
         },
         "decode": {
             "tokens_per_s_decode_only": T / (dec_ms * 1e-3),

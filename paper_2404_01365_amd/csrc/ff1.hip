@@ -161,17 +161,24 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             // rows 4j + rrow of the patch, 16 bytes per lane
             const int tok0 = m0 + wm * (32 * MI) + mi * 32 + rrow;
+            // all eight reads leave together; each store waits for its own row only (LDS returns in order)
+            f32x4_t pv[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                f32x4_t v;
                 const int row = 4 * j + rrow;
-                asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(patch + (uint32_t)(row * 256 + ((rch ^ (row & 15)) * 16))) : "memory");
-                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v) :: "memory");
-                const int tok = tok0 + 4 * j;
-                if (tok < p.M && ncol < p.F)
-                    *(f32x4_t *)(p.Z + (int64_t)tok * p.ldz + ncol) = v;
-                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("ds_read_b128 %0, %1" : "=v"(pv[j]) : "v"(patch + (uint32_t)(row * 256 + ((rch ^ (row & 15)) * 16))) : "memory");
             }
+#define FF1_PATCH_STORE(j_)                                                                          \
+            {                                                                                        \
+                asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(pv[j_]) : "n"(7 - (j_)) : "memory");     \
+                const int tok = tok0 + 4 * (j_);                                                     \
+                if (tok < p.M && ncol < p.F)                                                         \
+                    *(f32x4_t *)(p.Z + (int64_t)tok * p.ldz + ncol) = pv[j_];                        \
+                __builtin_amdgcn_sched_barrier(0);                                                   \
+            }
+            FF1_PATCH_STORE(0) FF1_PATCH_STORE(1) FF1_PATCH_STORE(2) FF1_PATCH_STORE(3)
+            FF1_PATCH_STORE(4) FF1_PATCH_STORE(5) FF1_PATCH_STORE(6) FF1_PATCH_STORE(7)
+#undef FF1_PATCH_STORE
         }
         if (PLAIN)
             return true;
