@@ -220,6 +220,26 @@ int griffin_ff_prompt_out(const float *Z, int64_t ldz, int64_t total_tokens, int
                           int64_t ldy, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The whole prompt phase of one FF block in one call (Section 4.2 and Section 5.1): Z = FF_1(X)
+ * is formed once and serves both the selection of the expert neurons (as griffin_prefill_select:
+ * Section 4.1, Eq. 6, top-k per sequence) and the prompt's own output through the FULL block
+ * (as griffin_ff_prompt_out: Y = Z W_2^T + b_2, Eq. 1).  Same results as the two calls one after
+ * the other; on the matrix-core path the bf16 copy of Z that the second product reads is written
+ * by the first product's own epilogue instead of by a pass over Z.
+ *   L, X, ldx, cu_seqlens_host, n_seqs, k, idx_out, s_out   as in griffin_prefill_select
+ *   W2p, ldw        the paper's W_2, [d][L->n] (row c = output feature c), in L->dtype, row stride
+ *                   ldw elements; L->b2 is added when it is not NULL
+ *   Y, ldy          [total_tokens][d] in L->dtype, row stride ldy elements
+ *   workspace       griffin_prompt_phase_workspace_bytes(L, total_tokens, n_seqs) bytes, 256-byte
+ *                   aligned; Z lives there (fp32 [total_tokens][L->n]) and is not returned
+ */
+size_t griffin_prompt_phase_workspace_bytes(const griffin_layer *L, int64_t total_tokens, int32_t n_seqs);
+int griffin_prompt_phase(const griffin_layer *L, const void *W2p, int64_t ldw, const void *X, int64_t ldx,
+                         const int32_t *cu_seqlens_host, int32_t n_seqs, int32_t k,
+                         int32_t *idx_out, float *s_out, void *Y, int64_t ldy,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Instrumentation for measurement (the generation phase is where the time goes, Section 5.2):
  * the next griffin_ff_decode* call made by this thread records, on that call's stream,
  * event_begin just before its weight-streaming kernel, event_mid between that kernel and the

@@ -46,7 +46,7 @@ def _load() -> ctypes.CDLL:
     import torch  # noqa: F401
     if not os.path.exists(LIB_PATH):
         raise ImportError(
-            "%s is missing: build it with `python -m paper_2404_01365_amd.build` "
+            "%s is missing: build it with `python paper_2404_01365_amd/build.py` "
             "(there is no fallback path)" % LIB_PATH)
     return ctypes.CDLL(LIB_PATH)
 
@@ -75,6 +75,8 @@ _SIGS = {
     "griffin_trace_next_decode": (ctypes.c_int, [_vp, _vp, _vp]),
     "griffin_prompt_out_workspace_bytes": (_sz, [_i64, _i32, _i32]),
     "griffin_ff_prompt_out": (ctypes.c_int, [_vp, _i64, _i64, _i32, _i32, _i32, _vp, _i64, _vp, _vp, _i64, _vp, _sz, _vp]),
+    "griffin_prompt_phase_workspace_bytes": (_sz, [_LP, _i64, _i32]),
+    "griffin_prompt_phase": (ctypes.c_int, [_LP, _vp, _i64, _vp, _i64, _IP, _i32, _i32, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
     "griffin_ff_decode": (ctypes.c_int, [_LP, _vp, _vp, _i32, _vp, _sz, _vp]),
     "griffin_ff_decode_multi": (ctypes.c_int, [_LP, _i32, _vp, _vp, _vp, _sz, _vp]),
     "griffin_ff_decode_indexed": (ctypes.c_int, [_LP, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
@@ -229,6 +231,22 @@ def griffin_ff_decode_indexed(L: griffin_layer, idx, k: int, batch: int, x, y, *
     _check(lib.griffin_ff_decode_indexed(ctypes.byref(L), _ptr(idx), k, batch, _ptr(x), _ptr(y),
                                          _ptr(workspace), _nbytes(workspace), _stream(stream)),
            "griffin_ff_decode_indexed")
+
+
+def griffin_prompt_phase_workspace_bytes(L: griffin_layer, total_tokens: int, n_seqs: int) -> int:
+    return int(lib.griffin_prompt_phase_workspace_bytes(ctypes.byref(L), total_tokens, n_seqs))
+
+
+def griffin_prompt_phase(L: griffin_layer, W2p, X, cu_seqlens: Sequence[int], k: int, idx_out, Y, *,
+                         s_out=None, workspace, ldx: Optional[int] = None, stream=None) -> None:
+    """Selection and the prompt's own output from one Z (W2p is the paper's W_2, [d][d_ff])."""
+    n_seqs = len(cu_seqlens) - 1
+    if ldx is None:
+        ldx = X.stride(0) if X is not None and X.dim() == 2 else L.d
+    st = lib.griffin_prompt_phase(ctypes.byref(L), _ptr(W2p), W2p.stride(0), _ptr(X), ldx, _cu_array(cu_seqlens),
+                                  n_seqs, k, _ptr(idx_out), _ptr(s_out), _ptr(Y), Y.stride(0),
+                                  _ptr(workspace), _nbytes(workspace), _stream(stream))
+    _check(st, "griffin_prompt_phase")
 
 
 def griffin_trace_next_decode(event_begin: Optional[int], event_mid: Optional[int],

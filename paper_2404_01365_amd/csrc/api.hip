@@ -289,6 +289,65 @@ int griffin_ff_prompt_out(const float *Z, int64_t ldz, int64_t total_tokens, int
                       (float *)workspace, workspace_bytes, (hipStream_t)stream);
 }
 
+size_t griffin_prompt_phase_workspace_bytes(const griffin_layer *L, int64_t total_tokens, int32_t n_seqs)
+{
+    if (check_layer(L) != GRIFFIN_OK || total_tokens < 0 || total_tokens > ((int64_t)1 << 30) || n_seqs < 1 ||
+        n_seqs > GRIFFIN_MAX_SEQS)
+        return 0;
+    const size_t first = plan_prefill(*L, total_tokens, n_seqs, false).total;
+    return first + align256(total_tokens > 0 ? ff2_workspace_bytes(total_tokens, L->n, L->d) : 0);
+}
+
+int griffin_prompt_phase(const griffin_layer *L, const void *W2p, int64_t ldw, const void *X, int64_t ldx,
+                         const int32_t *cu_seqlens_host, int32_t n_seqs, int32_t k,
+                         int32_t *idx_out, float *s_out, void *Y, int64_t ldy,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_layer(L);
+    if (rc != GRIFFIN_OK)
+        return rc;
+    SeqTable seqs;
+    int64_t total = 0;
+    if ((rc = fill_seq_table(cu_seqlens_host, n_seqs, seqs, &total)) != GRIFFIN_OK)
+        return rc;
+    if (!idx_out || !W2p || !Y || (total > 0 && !X))
+        return GRIFFIN_EINVAL;
+    if (k < 1 || k > L->n)
+        return GRIFFIN_ESHAPE;
+    if (ldx < L->d || ldx % 8 != 0 || !aligned16(X) || total > (int64_t)1 << 30 || ldw < L->n || ldy < L->d)
+        return GRIFFIN_ESHAPE;
+    const bool bf16 = L->dtype == GRIFFIN_BF16;
+    const bool tiles = bf16 && L->n % 8 == 0 && L->d % 4 == 0 && ldw % 8 == 0 && aligned16(W2p);
+    if (!tiles && total > ((int64_t)1 << 18))
+        return GRIFFIN_EUNSUPPORTED;
+    const PrefillPlan pl = plan_prefill(*L, total, n_seqs, false);
+    const size_t second = total > 0 ? ff2_workspace_bytes(total, L->n, L->d) : 0;
+    if (!workspace || workspace_bytes < pl.total + align256(second) || ((uintptr_t)workspace & 255))
+        return GRIFFIN_EWORKSPACE;
+
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    float *Z = (float *)(ws + pl.off_z);
+    float *rowpart = (float *)(ws + pl.off_rowpart);
+    float *w = (float *)(ws + pl.off_w);
+    float *s2part = (float *)(ws + pl.off_s2part);
+    float *s = (float *)(ws + pl.off_s);
+    float *ws2 = (float *)(ws + pl.total);
+
+    // the second product reads a bf16 copy of Z from the head of its workspace: let the first
+    // product's epilogue write it there when both kernels agree on the shape
+    const bool fuse = total > 0 && ff2_takes_zb(Z, L->n, total, L->n, L->d, bf16, W2p, ldw) &&
+                      ff1_can_write_zb(*L, ldx, Z, L->n);
+    int32_t nt = 0;
+    if ((rc = launch_ff1(*L, X, ldx, total, Z, L->n, rowpart, &nt, st, fuse ? (uint16_t *)ws2 : nullptr, L->n)) != GRIFFIN_OK)
+        return rc;
+    if ((rc = launch_stat(Z, L->n, rowpart, nt, total, L->n, seqs, pl.rc, w, s2part, s, s_out, st)) != GRIFFIN_OK)
+        return rc;
+    if ((rc = launch_topk(s, n_seqs, L->n, k, idx_out, st)) != GRIFFIN_OK)
+        return rc;
+    return launch_ff2(Z, L->n, total, L->n, L->d, bf16, W2p, ldw, L->b2, Y, ldy, ws2, second, st, fuse);
+}
+
 int griffin_trace_next_decode(void *event_begin, void *event_mid, void *event_end)
 {
     set_decode_probe((hipEvent_t)event_begin, (hipEvent_t)event_mid, (hipEvent_t)event_end);

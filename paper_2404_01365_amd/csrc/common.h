@@ -110,8 +110,10 @@ int set_hip_error(hipError_t e, const char *what);   // records text, returns GR
 int check_launch(const char *what);                  // hipGetLastError -> status
 
 // launchers (one per source file); all return a griffin_status
+// Zb (optional): a bf16 copy of Z [M][ldzb] written by the same epilogue when ff1_can_write_zb() says so
 int launch_ff1(const griffin_layer &L, const void *X, int64_t ldx, int64_t M, float *Z, int64_t ldz,
-               float *rowpart, int32_t *nt_out, hipStream_t st);
+               float *rowpart, int32_t *nt_out, hipStream_t st, uint16_t *Zb = nullptr, int64_t ldzb = 0);
+bool ff1_can_write_zb(const griffin_layer &L, int64_t ldx, const float *Z, int64_t ldz);
 int ff1_ntiles(const griffin_layer &L);
 int launch_stat(const float *Z, int64_t ldz, const float *rowpart, int nt, int64_t M, int32_t F,
                 const SeqTable &seqs, int rc, float *w, float *s2part, float *s, float *s_out,
@@ -130,8 +132,11 @@ bool gemm_nt_partials_ok(int64_t M, int32_t N, int32_t K, int64_t lda, int64_t l
 void gemm_nt_split_plan(int64_t M, int32_t N, int32_t K, int *splits, int *kt_per_split);
 int launch_gemm_nt_partials(const void *A, int64_t lda, const void *B, int64_t ldb, int64_t M, int32_t N, int32_t K,
                             int splits, int kt_per_split, float *C, hipStream_t st);
+// zb_ready: the bf16 copy of Z already sits at the head of ws (written by the first GEMM's epilogue)
 int launch_ff2(const float *Z, int64_t ldz, int64_t M, int32_t F, int32_t d, bool bf16, const void *W2p,
-               int64_t ldw, const void *b2, void *Y, int64_t ldy, float *ws, size_t ws_bytes, hipStream_t st);
+               int64_t ldw, const void *b2, void *Y, int64_t ldy, float *ws, size_t ws_bytes, hipStream_t st,
+               bool zb_ready = false);
+bool ff2_takes_zb(const float *Z, int64_t ldz, int64_t M, int32_t F, int32_t d, bool bf16, const void *W2p, int64_t ldw);
 size_t ff2_workspace_bytes(int64_t M, int32_t F, int32_t d);
 
 struct DecodeJob {

@@ -31,7 +31,8 @@ constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 struct Ff1Params {
     const void *X, *Wg, *W1, *bg, *b1;
     float *Z, *rowpart;
-    int64_t ldx, ldw, ldz;
+    uint16_t *Zb;                    // optional bf16 copy of Z [M][ldzb] for the prompt-output product, or NULL
+    int64_t ldx, ldw, ldz, ldzb;
     int32_t M, F, d, nt, mt;
     int32_t splits, kt_per_split;    // ranges of the contraction (1 for the activations) and 64-wide k-tiles per range
 };
@@ -172,8 +173,15 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
             {                                                                                        \
                 asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(pv[j_]) : "n"(7 - (j_)) : "memory");     \
                 const int tok = tok0 + 4 * (j_);                                                     \
-                if (tok < p.M && ncol < p.F)                                                         \
+                if (tok < p.M && ncol < p.F) {                                                       \
                     *(f32x4_t *)(p.Z + (int64_t)tok * p.ldz + ncol) = pv[j_];                        \
+                    if (!PLAIN && p.Zb) {                                                            \
+                        uint2 h_;                                                                    \
+                        h_.x = f32_to_bf16_bits(pv[j_][0]) | (f32_to_bf16_bits(pv[j_][1]) << 16);    \
+                        h_.y = f32_to_bf16_bits(pv[j_][2]) | (f32_to_bf16_bits(pv[j_][3]) << 16);    \
+                        *(uint2 *)(p.Zb + (int64_t)tok * p.ldzb + ncol) = h_;                        \
+                    }                                                                                \
+                }                                                                                    \
                 __builtin_amdgcn_sched_barrier(0);                                                   \
             }
             FF1_PATCH_STORE(0) FF1_PATCH_STORE(1) FF1_PATCH_STORE(2) FF1_PATCH_STORE(3)
@@ -441,7 +449,9 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
             FF1_LOAD_ONE(1, q)
         // k-tile 0 has landed when only the first half of k-tile 1 and (from the second tile on) the
         // epilogue's stores, all issued after it, are still outstanding
-        if (stores_known)
+        if (stores_known && !PLAIN && p.Zb)      // twice the Z stores: more than the counter holds, 63 is as good
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(H1 + EPI_STORES + MI * 8 > 63 ? 63 : H1 + EPI_STORES + MI * 8));
+        else if (stores_known)
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(H1 + EPI_STORES));
         else
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(H1));
@@ -789,12 +799,23 @@ static void launch_mfma_act(const Ff1Params &p, int act, bool gated, hipStream_t
     }
 }
 
+// Will the first GEMM's own epilogue leave a bf16 copy of Z beside the fp32 one?  Only the direct-to-LDS
+// kernel's usual store path does (bf16 block, d in whole k-tiles, no biases, 16-byte aligned rows of Z).
+bool ff1_can_write_zb(const griffin_layer &L, int64_t ldx, const float *Z, int64_t ldz)
+{
+    const bool ktail = L.d % 64 != 0 || ldx > (1 << 21) || L.ld > (1 << 21);
+    const bool vec = ((L.n | (int32_t)ldz) & 3) == 0 && ((uintptr_t)Z & 15) == 0;
+    return L.dtype == GRIFFIN_BF16 && !ktail && vec && !L.b1 && !L.bg;
+}
+
 int launch_ff1(const griffin_layer &L, const void *X, int64_t ldx, int64_t M, float *Z, int64_t ldz,
-               float *rowpart, int32_t *nt_out, hipStream_t st)
+               float *rowpart, int32_t *nt_out, hipStream_t st, uint16_t *Zb, int64_t ldzb)
 {
     Ff1Params p;
     p.X = X; p.Wg = L.Wg; p.W1 = L.W1; p.bg = L.bg; p.b1 = L.b1;
     p.Z = Z; p.rowpart = rowpart;
+    p.Zb = (Zb && ff1_can_write_zb(L, ldx, Z, ldz)) ? Zb : nullptr;
+    p.ldzb = ldzb;
     p.ldx = ldx; p.ldw = L.ld; p.ldz = ldz;
     p.M = (int32_t)M; p.F = L.n; p.d = L.d;
     p.splits = 1; p.kt_per_split = L.d / 64;
@@ -862,6 +883,7 @@ int launch_gemm_nt_partials(const void *A, int64_t lda, const void *B, int64_t l
     Ff1Params p;
     p.X = A; p.Wg = nullptr; p.W1 = B; p.bg = nullptr; p.b1 = nullptr;
     p.Z = C; p.rowpart = nullptr;
+    p.Zb = nullptr; p.ldzb = 0;
     p.ldx = lda; p.ldw = ldb; p.ldz = N;
     p.M = (int32_t)M; p.F = N; p.d = K;
     p.splits = splits; p.kt_per_split = kt_per_split;

@@ -287,8 +287,15 @@ size_t ff2_workspace_bytes(int64_t M, int32_t F, int32_t d)
     return need;
 }
 
+// Does the prompt-output product of this shape run from a bf16 copy of Z [M][F] at the head of its workspace?
+bool ff2_takes_zb(const float *Z, int64_t ldz, int64_t M, int32_t F, int32_t d, bool bf16, const void *W2p, int64_t ldw)
+{
+    return M >= 1 && ff2_dma_ok(Z, ldz, M, F, d, bf16, W2p, ldw);
+}
+
 int launch_ff2(const float *Z, int64_t ldz, int64_t M, int32_t F, int32_t d, bool bf16, const void *W2p,
-               int64_t ldw, const void *b2, void *Y, int64_t ldy, float *ws, size_t ws_bytes, hipStream_t st)
+               int64_t ldw, const void *b2, void *Y, int64_t ldy, float *ws, size_t ws_bytes, hipStream_t st,
+               bool zb_ready)
 {
     if (M == 0)
         return GRIFFIN_OK;
@@ -305,11 +312,13 @@ int launch_ff2(const float *Z, int64_t ldz, int64_t M, int32_t F, int32_t d, boo
             return GRIFFIN_EWORKSPACE;
         uint16_t *Zb = (uint16_t *)ws;
         p.part = (float *)((char *)ws + zb_bytes);
-        const int64_t oct = M * F / 8;
-        hipLaunchKernelGGL(ff2_z_to_bf16_kernel, dim3((unsigned)((oct + 255) / 256)), dim3(256), 0, st, Z, ldz, M, F, Zb);
-        int rc = check_launch("ff2_z_to_bf16_kernel");
-        if (rc != GRIFFIN_OK)
-            return rc;
+        int rc = GRIFFIN_OK;
+        if (!zb_ready) {
+            const int64_t oct = M * F / 8;
+            hipLaunchKernelGGL(ff2_z_to_bf16_kernel, dim3((unsigned)((oct + 255) / 256)), dim3(256), 0, st, Z, ldz, M, F, Zb);
+            if ((rc = check_launch("ff2_z_to_bf16_kernel")) != GRIFFIN_OK)
+                return rc;
+        }
         if ((rc = launch_gemm_nt_partials(Zb, F, W2p, ldw, M, d, F, p.splits, per, p.part, st)) != GRIFFIN_OK)
             return rc;
         const int64_t quads = (int64_t)M * d / 4;

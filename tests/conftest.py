@@ -8,8 +8,22 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+def _build_if_missing():
+    """The tests load the library that is built; only when none is there do they build it (the build
+    script is loaded by path, since importing the package needs the library)."""
+    lib = os.path.join(ROOT, "paper_2404_01365_amd", "libgriffin.so")
+    if os.path.exists(lib):
+        return
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("griffin_hip_build", os.path.join(ROOT, "paper_2404_01365_amd", "build.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    mod.build(verbose=True)
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    _build_if_missing()
 
 
 def _has_gpu() -> bool:
