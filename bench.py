@@ -256,7 +256,7 @@ def main():
             t["Lf"], t["Lft"] = [], []
 
     # the prompt's own full-width output Y = Z W_2^T (Section 5.1), outside the timed region
-    prompt_out_us = None
+    prompt_out_us = prompt_phase_us = None
     if not args.skip_full_width:
         t0l = layers[0]
         Zbuf = torch.empty((S, F), dtype=torch.float32, device="cuda")
@@ -272,7 +272,18 @@ def main():
         pe[1].record()
         torch.cuda.synchronize()
         prompt_out_us = pe[0].elapsed_time(pe[1]) * 1e3 / 5
-        del Zbuf, W2p, Yp
+        # ... and the whole prompt phase in one call (selection + output from one Z, Section 4.2 + 5.1)
+        ws_pp = torch.empty(G.griffin_prompt_phase_workspace_bytes(t0l["L"], S, 1), dtype=torch.uint8, device="cuda")
+        idx_pp = torch.empty_like(t0l["idx"])
+        for rep in range(6):
+            if rep == 1:
+                pe[0].record()
+            G.griffin_prompt_phase(t0l["L"], W2p, t0l["X"], cu, k, idx_pp, Yp, workspace=ws_pp, stream=stream)
+        pe[1].record()
+        torch.cuda.synchronize()
+        prompt_phase_us = pe[0].elapsed_time(pe[1]) * 1e3 / 5
+        assert bool((idx_pp == t0l["idx"]).all()), "prompt phase and prefill_select disagree on the expert set"
+        del Zbuf, W2p, Yp, ws_pp
 
     # further rows measured outside the timed region: the static weight-norm selector (Section 5.1
     # setup) and one shared set decoded for a batch of 16 rows (Section 5.3, Eq. 7)
@@ -404,6 +415,8 @@ def main():
         "select_us_per_layer": sel_ms * 1e3 / n_layers,
         "prompt_out": None if prompt_out_us is None else {
             "us_per_layer": prompt_out_us, "TFLOPs": 2.0 * S * F * d / (prompt_out_us * 1e-6) / 1e12},
+        "prompt_phase_one_call": None if prompt_phase_us is None else {
+            "us_per_layer": prompt_phase_us, "TFLOPs": (4.0 + 2.0) * S * F * d / (prompt_phase_us * 1e-6) / 1e12},
     }
     if extras:
         out.update(extras)

@@ -152,6 +152,36 @@ def test_selectors_and_prompt_out_reject_bad_arguments_without_hip():
     assert po(FAKE, 688, 64, 688, 256, 7, FAKE, 688, None, FAKE, 256, None, 0, None) == G.EINVAL
 
 
+def test_prompt_phase_rejects_bad_arguments_without_hip():
+    L = mk()
+    cu = (ctypes.c_int32 * 2)(0, 64)
+    big = 1 << 40
+    # L, W2p, ldw, X, ldx, cu, n_seqs, k, idx_out, s_out, Y, ldy, ws, ws_bytes, stream
+    pp = lambda **kw: G.lib.griffin_prompt_phase(
+        ctypes.byref(kw.get("L", L)), kw.get("W2p", FAKE), kw.get("ldw", 688), kw.get("X", FAKE), kw.get("ldx", 256), cu, 1,
+        kw.get("k", 344), kw.get("idx", FAKE), None, kw.get("Y", FAKE), kw.get("ldy", 256), kw.get("ws", FAKE),
+        kw.get("ws_bytes", big), None)
+    assert pp(W2p=None) == G.EINVAL
+    assert pp(Y=None) == G.EINVAL
+    assert pp(idx=None) == G.EINVAL
+    assert pp(X=None) == G.EINVAL
+    assert pp(L=mk(W1=None)) == G.EINVAL
+    assert pp(k=0) == G.ESHAPE
+    assert pp(k=689) == G.ESHAPE
+    assert pp(ldw=600) == G.ESHAPE            # W_2's rows shorter than D_ff
+    assert pp(ldy=100) == G.ESHAPE
+    assert pp(ldx=100) == G.ESHAPE
+    assert pp(ws=None) == G.EWORKSPACE
+    assert pp(ws_bytes=1024) == G.EWORKSPACE
+    assert pp(ws=FAKE + 16) == G.EWORKSPACE
+    # the workspace holds what griffin_prefill_select needs (Z included) and what the output product needs
+    Lb = mk(d=4096, n=11008, dtype=G.BF16)
+    both = G.griffin_prompt_phase_workspace_bytes(Lb, 512, 1)
+    assert both >= G.griffin_prefill_workspace_bytes(Lb, 512, 1, False) + G.griffin_prompt_out_workspace_bytes(512, 11008, 4096)
+    assert both % 256 == 0
+    assert G.griffin_prompt_phase_workspace_bytes(mk(d=250), 512, 1) == 0
+
+
 def test_batch_decode_workspace_covers_the_matrix_core_path():
     # 16 rows through one block: partial rows [16][ranges][d] plus the table of Z [n][16]
     d, n = 4096, 5504

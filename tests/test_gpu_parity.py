@@ -418,6 +418,58 @@ def test_prompt_output_uses_the_full_block(dtype, d, F, S, bias):
     assert max_rel(Y_ref[0], y0) <= 1e-12
 
 
+@pytest.mark.parametrize("dtype,d,F,lens,k,gated,bias", [
+    (synth.DT_BF16, 512, 1024, [300, 77], 400, True, False),    # one pass: the first product leaves the bf16 copy
+    (synth.DT_BF16, 256, 4096, [40], 2048, True, False),        # 128-token tile, contraction cut into ranges
+    (synth.DT_BF16, 384, 2048, [10, 0, 290], 1000, False, False),  # Eq. 2 block, an empty prompt in the middle
+    (synth.DT_BF16, 384, 2048, [300], 1000, True, True),        # biases: Z is converted by its own pass
+    (synth.DT_BF16, 136, 264, [70], 100, True, False),          # k tail: register-staged kernels
+    (synth.DT_F32, 256, 688, [64], 344, True, True),            # config-0 shape, fp32
+])
+def test_prompt_phase_is_selection_plus_prompt_output_from_one_z(dtype, d, F, lens, k, gated, bias):
+    """Section 4.2 + Section 5.1 in one call: the sets of griffin_prefill_select, the output of
+    griffin_ff_prompt_out, both checked against the oracle and, bit for bit, against the two calls."""
+    act = synth.ACT_SILU
+    S = sum(lens)
+    c = synth.small_case(d * 3 + F + S, d, F, S, dtype, with_bias=bias)
+    Wg = c["Wg"] if gated else None
+    bg = c.get("bg") if gated else None
+    b1, b2 = c.get("b1"), c.get("b2")
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    live = [b for b in range(len(lens)) if lens[b] > 0]
+    W1 = c["W1"].copy()
+    _, s_ref_live = open_margin([c["X"][cu[b]:cu[b + 1]] for b in live], Wg, W1, act, dtype, [k], bg, b1)
+    L, _ = dev_layer(Wg, W1, c["W2"], act, dtype, bg, b1, b2)
+    Xd = to_dev(c["X"], dtype)
+    W2p = to_dev(np.ascontiguousarray(c["W2"].T), dtype)          # the paper's W_2: [d][D_ff]
+    n_seqs = len(lens)
+    idx = torch.full((n_seqs, k), -1, dtype=torch.int32, device="cuda")
+    sd = torch.full((n_seqs, F), -1.0, dtype=torch.float32, device="cuda")
+    Y = torch.full((S, d), float("nan"), dtype=W2p.dtype, device="cuda")
+    ws = workspace(G.griffin_prompt_phase_workspace_bytes(L, S, n_seqs))
+    ws.fill_(0xFF)
+    G.griffin_prompt_phase(L, W2p, Xd, [int(v) for v in cu], k, idx, Y, s_out=sd, workspace=ws)
+    sync()
+    # against the oracle
+    Z_ref = oracle.ff1(c["X"], Wg, W1, act, bg, b1)
+    assert max_rel(to_host(Y), oracle.ff2(Z_ref, c["W2"], b2)) <= TOL_OUT[dtype]
+    s_got = sd.cpu().numpy().astype(np.float64)
+    for pos, b in enumerate(live):
+        assert boundary_report(s_ref_live[pos], k)[0] > 1e-3
+        assert max_rel(s_got[b], s_ref_live[pos]) <= TOL_S
+        np.testing.assert_array_equal(idx.cpu().numpy()[b], oracle.topk(s_ref_live[pos], k))
+    # against the two calls
+    idx2, s2, Z2 = run_prefill(L, Xd, cu, k)
+    Zd = torch.from_numpy(Z2.astype(np.float32)).cuda()
+    Y2 = torch.empty_like(Y)
+    G.griffin_ff_prompt_out(Zd, W2p, Y2, b2=to_dev(b2, dtype),
+                            workspace=workspace(G.griffin_prompt_out_workspace_bytes(S, F, d)))
+    sync()
+    np.testing.assert_array_equal(idx.cpu().numpy(), idx2)
+    assert np.array_equal(s_got, s2)
+    assert np.array_equal(to_host(Y), to_host(Y2))
+
+
 # ------------------------------------------------------------------ static and sampled selectors, set similarity
 @pytest.mark.parametrize("dtype,d,F,gated", [
     (synth.DT_BF16, 512, 1000, True), (synth.DT_BF16, 8, 5, True), (synth.DT_BF16, 4096, 700, False),
