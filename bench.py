@@ -31,7 +31,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=1, help="workload: 1 Llama-2-7B-shaped layer, 2 Gemma-7B-shaped layer, 3 Llama-2-13B-shaped stack of 40")
+    ap.add_argument("--config", type=int, default=1, help="workload: 1 Llama-2-7B-shaped layer, 2 Gemma-7B-shaped layer, 3 Llama-2-13B-shaped stack of 40, "
+                         "4 Mistral-7B-shaped stack of 8 with 16 sequences that keep their own sets")
     ap.add_argument("--k", type=int, default=0, help="kept neurons (default: the config's 50%% point)")
     ap.add_argument("--layers", type=int, default=0, help="layers to run (default: all of the config)")
     ap.add_argument("--probe-every", type=int, default=8, help="decode steps between kernel-duration probes")
@@ -102,6 +103,141 @@ def cpu_baseline(cfg, k, Wg, W1, W2, seconds_target=12.0):
     }
 
 
+def run_batched(args, cfg, torch, np, G, synth, hip):
+    """Config 4: B sequences with their own expert sets share every layer's weights.  One step =
+    selection for all layers (packed variable-length prompts, one set per sequence) + T decode
+    steps of B rows through every layer, each row through its own set, in ONE masked pass over the
+    full block per layer-step (the per-sequence sets cover almost the whole block between them, so
+    compact copies would stream B x the bytes; that variant is timed beside it, outside the region)."""
+    k = args.k or cfg.k
+    n_layers = args.layers or cfg.n_layers
+    T, d, F, B = cfg.decode_steps, cfg.d, cfg.d_ff, cfg.n_seqs
+    w = 2
+    up = lambda a: torch.from_numpy(synth.bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16)
+    stream = torch.cuda.current_stream().cuda_stream
+    layers, host_w0 = [], None
+    for l in range(n_layers):
+        Wg, W1, W2 = synth.layer_weights(cfg, l)
+        if l == 0:
+            host_w0 = (Wg, W1, W2)
+        X, cu = synth.packed_prompts(cfg, l)
+        xt = np.stack([synth.decode_inputs(cfg, l, b) for b in range(B)], axis=1)      # [T][B][d]
+        t = dict(Wg=up(Wg), W1=up(W1), W2=up(W2), X=up(X), xt=up(xt), cu=[int(v) for v in cu])
+        t["L"] = G.layer(t["W1"], t["W2"], t["Wg"], act=cfg.act)
+        t["idx"] = torch.empty((B, k), dtype=torch.int32, device="cuda")
+        t["y"] = torch.empty((T, B, d), dtype=torch.bfloat16, device="cuda")
+        layers.append(t)
+        del Wg, W1, W2
+    total = layers[0]["cu"][-1]
+    ws_pre = torch.empty(G.griffin_prefill_workspace_bytes(layers[0]["L"], total, B, False), dtype=torch.uint8, device="cuda")
+    ws_dec = torch.empty(G.griffin_decode_workspace_bytes(d, F, B), dtype=torch.uint8, device="cuda")   # sized for the whole block
+    esz = B * d * w
+    for t in layers:
+        t["xp"], t["yp"] = t["xt"].data_ptr(), t["y"].data_ptr()
+
+    per_step = (T * n_layers + args.probe_every - 1) // args.probe_every
+    pool = [(hip.event(), hip.event(), hip.event()) for _ in range(per_step * args.steps)]
+    probes, stage_ev = [], []
+
+    def step(record):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)] if record else None
+        if record:
+            ev[0].record()
+        for t in layers:
+            G.griffin_prefill_select(t["L"], t["X"], t["cu"], k, t["idx"], workspace=ws_pre, stream=stream)
+        if record:
+            ev[1].record()
+        for tok in range(T):
+            for li, t in enumerate(layers):
+                if record and (tok * n_layers + li) % args.probe_every == 0:
+                    pe = pool[len(probes)]
+                    probes.append(pe)
+                    G.griffin_trace_next_decode(*pe)
+                G.griffin_ff_decode_indexed(t["L"], t["idx"], k, B, t["xp"] + tok * esz, t["yp"] + tok * esz,
+                                            workspace=ws_dec, stream=stream)
+        if record:
+            ev[2].record()
+            stage_ev.append(ev)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    # beside it, outside the timed region: every sequence through its own compact block (one layer)
+    multi_us = None
+    if not args.skip_full_width:
+        t0l = layers[0]
+        Cs, keep = [], []
+        for b in range(B):
+            blk = torch.empty((k, 3, d), dtype=torch.bfloat16, device="cuda")
+            C = G.layer(blk[:, 1], blk[:, 2], blk[:, 0], act=cfg.act)
+            G.griffin_compact(t0l["L"], t0l["idx"][b], k, C, stream=stream)
+            Cs.append(C); keep.append(blk)
+        ws_m = torch.empty(G.griffin_decode_workspace_bytes(d, k, B), dtype=torch.uint8, device="cuda")
+        me = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        for rep in range(11):
+            if rep == 1:
+                me[0].record()
+            G.griffin_ff_decode_multi(Cs, t0l["xp"] + (rep % T) * esz, t0l["yp"] + (rep % T) * esz, workspace=ws_m, stream=stream)
+        me[1].record()
+        torch.cuda.synchronize()
+        multi_us = me[0].elapsed_time(me[1]) * 1e3 / 10
+        del Cs, keep, ws_m
+
+    sel_ms = sum(e[0].elapsed_time(e[1]) for e in stage_ev) / len(stage_ev)
+    dec_ms = sum(e[1].elapsed_time(e[2]) for e in stage_ev) / len(stage_ev)
+    raw_main = [hip.elapsed_ms(a, m) * 1e3 for a, m, e in probes]
+    raw_tok = [hip.elapsed_ms(a, e) * 1e3 for a, m, e in probes]
+    n_tok = args.steps * T * n_layers
+    span_us = sum(e[1].elapsed_time(e[2]) for e in stage_ev) * 1e3
+    Bp = sum(raw_tok) / len(raw_tok)
+    u = (span_us - len(probes) * Bp) / max(n_tok - len(probes), 1)
+    event_overhead_us = max((Bp - u) / 2.0, 0.0)
+    kern_us = sorted(max(v - event_overhead_us, 0.0) for v in raw_main)
+    avg_us = sum(kern_us) / len(kern_us)
+    # the masked pass reads the whole block once per layer-step, the B rows of x, and writes B rows of y
+    alg_bytes = 3 * F * d * w + 2 * B * d * w
+    achieved = alg_bytes / (avg_us * 1e-6) / 1e9
+    out = {
+        "metric": "pruned-FF decode tokens/s + achieved HBM GB/s; select \u00b5s/layer (prefill)",
+        "value": args.steps * T * B / wall,
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {
+            "workload": "config %d: %s, d=%d D_ff=%d, %d prompts of %d..%d tokens (%d in all), keep k=%d per sequence, "
+                        "batch %d, %d decode steps, %d layer(s)" % (cfg.cid, cfg.name, d, F, B, cfg.len_range[0], cfg.len_range[1],
+                                                                    total, k, B, T, n_layers),
+            "decode": "one masked pass over the full block per layer-step (griffin_ff_decode_indexed)",
+            "cache": "cold (%.1f GB of weights per step)" % (n_layers * 3 * F * d * w / 1e9),
+        },
+        "roofline": {
+            "bound": "hbm", "kernel": "masked pass: mask kernels + ff_batch_gu_kernel + ff_batch_down_kernel",
+            "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": None, "algorithmic_bytes_per_launch": alg_bytes,
+            "avg_kernel_us": avg_us, "median_kernel_us": kern_us[len(kern_us) // 2], "launches_timed": len(kern_us),
+            "event_cost_us": event_overhead_us, "unprobed_us_per_layer_step": u,
+        },
+        "decode": {
+            "tokens_per_s_decode_only": T * B / (dec_ms * 1e-3),
+            "us_per_layer_step": dec_ms * 1e3 / (T * n_layers),
+            "per_sequence_compact_blocks_us_per_layer_step": multi_us,
+            "per_sequence_compact_blocks_GBps": None if multi_us is None else B * 3 * k * d * w / (multi_us * 1e-6) / 1e9,
+        },
+        "select_us_per_layer": sel_ms * 1e3 / n_layers,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, k, *host_w0)
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -122,8 +258,10 @@ def main():
 
     cfg = synth.CONFIGS[args.config]
     if cfg.n_seqs != 1:
-        print("bench.py: config %d is a batched parity case, not a bench line" % args.config, file=sys.stderr)
-        sys.exit(2)
+        if cfg.dtype != synth.DT_BF16:
+            print("bench.py: config %d is a parity case, not a bench line" % args.config, file=sys.stderr)
+            sys.exit(2)
+        return run_batched(args, cfg, torch, np, G, synth, hip)
     k = args.k or cfg.k
     n_layers = args.layers or cfg.n_layers
     T, d, F, S = cfg.decode_steps, cfg.d, cfg.d_ff, cfg.prompt_len
