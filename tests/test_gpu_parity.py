@@ -596,6 +596,7 @@ def test_decode_takes_the_maximum_batch():
     (1024, 300, 100, 7, False, True),      # Eq. 2 block with biases, 7 of 16 rows
     (2048, 999, 500, 19, True, True),      # two groups of rows (16 + 3), odd block size
     (512, 64, 64, 5, True, False),         # every row keeps the whole block
+    (512, 9000, 150, 6, True, False),      # a longer block, lists partly unsorted
 ])
 def test_indexed_decode_masked_pass_matches_oracle(d, n, k, B, gated, bias):
     """Rows with their own sets inside one block, one masked pass over the block (workspace sized for it)."""
@@ -605,7 +606,8 @@ def test_indexed_decode_masked_pass_matches_oracle(d, n, k, B, gated, bias):
     bg = c.get("bg") if gated else None
     L, _ = dev_layer(Wg, c["W1"], c["W2"], act, dtype, bg, c.get("b1"), c.get("b2"))
     rng = np.random.default_rng(B)
-    idx = np.stack([np.sort(rng.choice(n, k, replace=False)) for _ in range(B)]).astype(np.int32)
+    # the lists need not be ascending: odd rows are left in the order they were drawn
+    idx = np.stack([(np.sort if b % 2 == 0 else np.asarray)(rng.choice(n, k, replace=False)) for b in range(B)]).astype(np.int32)
     x = to_dev(c["xt"], dtype)
     y = torch.empty_like(x)
     G.griffin_ff_decode_indexed(L, torch.from_numpy(idx).cuda(), k, B, x, y,
