@@ -121,3 +121,67 @@ def test_prefill_sweep(c):
             np.testing.assert_array_equal(idx_h[b], oracle.topk(s_ref, k))
         elif k < F:
             assert np.min(s_h[b][idx_h[b]]) >= np.max(np.delete(s_h[b], idx_h[b]))
+
+
+def _set_cases(seed, count):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(count):
+        n = int(rng.integers(64, 1500))
+        out.append(dict(
+            d=int(rng.choice([512, 1024, 1536, 2560, 4096, 5120])),
+            n=n,
+            k=int(rng.integers(1, n + 1)),
+            act=ACTS[int(rng.integers(0, 3))],
+            gated=bool(rng.random() < 0.75),
+            bias=bool(rng.random() < 0.4),
+            batch=int(rng.choice([1, 2, 4, 5, 6, 16, 17, 40])),
+            mode=str(rng.choice(["transposed", "masked", "indexed", "multi"])),
+            seed=int(rng.integers(1, 1 << 30)),
+        ))
+    return out
+
+
+@pytest.mark.parametrize("c", _set_cases(303, 28),
+                         ids=lambda c: "%s-d%d-n%d-k%d-b%d-%s%s" % (c["mode"], c["d"], c["n"], c["k"], c["batch"],
+                                                                     "g" if c["gated"] else "u", "b" if c["bias"] else ""))
+def test_selected_set_decode_sweep(c):
+    """Rows through their selected sets (Eq. 4-5) by every route the library has: a compact block that
+    carries W2 in the paper's orientation (one row), index lists into the full block with the workspace
+    of the masked pass or the smaller one, and one compact block per row."""
+    dtype, d, n, k, B, act = synth.DT_BF16, c["d"], c["n"], c["k"], c["batch"], c["act"]
+    s = synth.small_case(c["seed"], d, n, 2, dtype, T=B, with_bias=c["bias"])
+    Wg = s["Wg"] if c["gated"] else None
+    bg = s.get("bg") if c["gated"] else None
+    b1, b2 = s.get("b1"), s.get("b2")
+    L, t = dev_layer(Wg, s["W1"], s["W2"], act, dtype, bg, b1, b2)
+    rng = np.random.default_rng(c["seed"])
+    shared = c["mode"] == "transposed"
+    sets = [np.sort(rng.choice(n, k, replace=False)).astype(np.int32) for _ in range(1 if shared else B)]
+    x = to_dev(s["xt"], dtype)
+    y = torch.full_like(x, float("nan"))
+    keep = []
+    if c["mode"] == "transposed":
+        C, ct = empty_compact(L, k, t, interleaved=bool(c["seed"] & 1), transposed="only")
+        G.griffin_compact(L, torch.from_numpy(sets[0]).cuda(), k, C)
+        ws = workspace(G.griffin_decode_workspace_bytes(d, k, 1))
+        for b in range(B):          # one row per call: the route that reads W2 in the paper's orientation
+            G.griffin_ff_decode(C, x[b], y[b], 1, workspace=ws)
+    elif c["mode"] == "multi":
+        Cs = []
+        for b in range(B):
+            Cb, kb = empty_compact(L, k, t, interleaved=bool(c["seed"] & 1))
+            G.griffin_compact(L, torch.from_numpy(sets[b]).cuda(), k, Cb)
+            Cs.append(Cb); keep.append(kb)
+        G.griffin_ff_decode_multi(Cs, x, y, workspace=workspace(G.griffin_decode_workspace_bytes(d, k, B)))
+    else:
+        idx = torch.from_numpy(np.stack(sets)).cuda()
+        nbytes = G.griffin_decode_workspace_bytes(d, n if c["mode"] == "masked" else k, B)
+        G.griffin_ff_decode_indexed(L, idx, k, B, x, y, workspace=workspace(nbytes))
+    torch.cuda.synchronize()
+    got = to_host(y)
+    for b in range(B):
+        e = sets[0] if shared else sets[b]
+        sub = lambda a: None if a is None else a[e]
+        ref = oracle.ff_decode(s["xt"][b], sub(Wg), s["W1"][e], s["W2"][e], act, sub(bg), sub(b1), b2)
+        assert max_rel(got[b], ref) <= TOL_OUT[dtype], (c, b)
