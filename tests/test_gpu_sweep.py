@@ -185,3 +185,62 @@ def test_selected_set_decode_sweep(c):
         sub = lambda a: None if a is None else a[e]
         ref = oracle.ff_decode(s["xt"][b], sub(Wg), s["W1"][e], s["W2"][e], act, sub(bg), sub(b1), b2)
         assert max_rel(got[b], ref) <= TOL_OUT[dtype], (c, b)
+
+
+def _phase_cases(seed, count):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(count):
+        n_seqs = int(rng.choice([1, 1, 2, 3]))
+        F = int(rng.integers(1, 12)) * 64 if rng.random() < 0.6 else int(rng.integers(1, 700))
+        out.append(dict(
+            dtype=synth.DT_BF16 if rng.random() < 0.8 else synth.DT_F32,
+            d=int(rng.choice([8, 64, 128, 192, 256, 384, 512, 1024])),
+            F=F,
+            lens=[int(v) for v in rng.integers(0, 400, size=n_seqs)],
+            act=ACTS[int(rng.integers(0, 3))],
+            gated=bool(rng.random() < 0.75),
+            bias=bool(rng.random() < 0.3),
+            seed=int(rng.integers(1, 1 << 30)),
+        ))
+    return out
+
+
+@pytest.mark.parametrize("c", _phase_cases(404, 20),
+                         ids=lambda c: "%s-d%d-F%d-%s-%s%s" % ("bf16" if c["dtype"] == synth.DT_BF16 else "f32", c["d"], c["F"],
+                                                                "+".join(map(str, c["lens"])), "g" if c["gated"] else "u", "b" if c["bias"] else ""))
+def test_prompt_phase_sweep(c):
+    """Selection and the prompt's own output from one Z (Section 4.2 + Section 5.1), random shapes."""
+    dtype, d, F, lens, act = c["dtype"], c["d"], c["F"], c["lens"], c["act"]
+    total = sum(lens)
+    s = synth.small_case(c["seed"], d, F, max(total, 1), dtype, with_bias=c["bias"])
+    Wg = s["Wg"] if c["gated"] else None
+    bg = s.get("bg") if c["gated"] else None
+    b1, b2 = s.get("b1"), s.get("b2")
+    L, _ = dev_layer(Wg, s["W1"], s["W2"], act, dtype, bg, b1, b2)
+    W2p = to_dev(np.ascontiguousarray(s["W2"].T), dtype)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    k = max(1, F // 2)
+    n_seqs = len(lens)
+    idx = torch.full((n_seqs, k), -1, dtype=torch.int32, device="cuda")
+    sd = torch.empty((n_seqs, F), dtype=torch.float32, device="cuda")
+    Y = torch.full((max(total, 1), d), float("nan"), dtype=W2p.dtype, device="cuda")
+    G.griffin_prompt_phase(L, W2p, to_dev(s["X"][:max(total, 1)], dtype), [int(v) for v in cu], k, idx, Y, s_out=sd,
+                           workspace=workspace(G.griffin_prompt_phase_workspace_bytes(L, total, n_seqs)))
+    torch.cuda.synchronize()
+    idx_h, s_h = idx.cpu().numpy(), sd.cpu().numpy().astype(np.float64)
+    if total > 0:
+        Z_ref = oracle.ff1(s["X"][:total], Wg, s["W1"], act, bg, b1)
+        assert max_rel(to_host(Y)[:total], oracle.ff2(Z_ref, s["W2"], b2)) <= TOL_OUT[dtype], c
+    for b in range(n_seqs):
+        if lens[b] == 0:
+            assert np.all(s_h[b] == 0.0) and idx_h[b].tolist() == list(range(k))
+            continue
+        s_ref = oracle.stat(Z_ref[cu[b]:cu[b + 1]])
+        if np.max(s_ref) > 0:
+            assert np.max(np.abs(s_h[b] - s_ref)) <= 2e-5 * np.max(s_ref), c
+        assert np.all(np.diff(idx_h[b]) > 0) and idx_h[b][0] >= 0 and idx_h[b][-1] < F
+        if boundary_report(s_ref, k)[0] > 1e-3:
+            np.testing.assert_array_equal(idx_h[b], oracle.topk(s_ref, k))
+        elif k < F:
+            assert np.min(s_h[b][idx_h[b]]) >= np.max(np.delete(s_h[b], idx_h[b]))
