@@ -289,10 +289,20 @@ __global__ __launch_bounds__(256) void ff_decode_reduce_kernel(const float *part
         return;
     const void *b2 = MULTI ? b2_multi.p[b] : b2_one;
     const float *base = part + (int64_t)b * P * d + c;
+    // four rows per lane on their way at once (256 partial rows: all of them); one load per trip of a
+    // loop would put that many memory latencies in a row.  Same order of additions as row by row.
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int pp = lane; pp < P; pp += 64) {
-        const float4 t = *(const float4 *)(base + (int64_t)pp * d);
-        acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+    for (int p0 = lane; p0 < P; p0 += 256) {
+        float4 t[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int pp = p0 + 64 * i;
+            t[i] = pp < P ? *(const float4 *)(base + (int64_t)pp * d) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc.x += t[i].x; acc.y += t[i].y; acc.z += t[i].z; acc.w += t[i].w;
+        }
     }
     float4 s;
     s.x = wave_sum(acc.x); s.y = wave_sum(acc.y); s.z = wave_sum(acc.z); s.w = wave_sum(acc.w);

@@ -262,7 +262,7 @@ __global__ __launch_bounds__(MAXT) void ff_batch_gu_kernel(BatchParams p)
 // No wave waits for another after the first barrier.
 constexpr int BD_ZLD = 520;              // elements per row of the Z tables in LDS
 constexpr int BD_RANGE = 480;            // neurons per workgroup before rounding to multiples of 8
-constexpr int BD_DEPTH = 3;              // ring slots per wave
+constexpr int BD_DEPTH = 3;              // ring slots per wave (a fourth, fitted into the LDS by trimming the tables, changed nothing)
 constexpr int BD_REGION = 66;            // 16-byte units per 8-row region: 1 KB of rows + 32 B, so that the four
                                          // regions a gather touches (rows 8q + i) start on different LDS banks
 constexpr int BD_SLOT = 4 * BD_REGION;   // a slot: 32 rows x 128 B in four regions
@@ -279,16 +279,17 @@ __global__ __launch_bounds__(BT_WAVES2 * 64) void ff_batch_down_kernel(BatchPara
     const int range = j_hi - j_lo;                 // <= 488 by the choice of NR
     const int S = (range + 31) >> 5;
 
-    // Z[j][b] fp32 -> hi/lo bf16 tables [b][j - j_lo], zero beyond the range
-    for (int i = tid; i < S * 32 * 16; i += BT_WAVES2 * 64) {
-        const int jr = i >> 4, b = i & 15;
-        const float v = jr < range ? z[(int64_t)(j_lo + jr) * 16 + b] : 0.0f;
-        const uint32_t h = f32_to_bf16_bits(v);
-        const float rest = v - bf16_bits_to_f32(h);
-        zhi[b * BD_ZLD + jr] = (uint16_t)h;
-        zlo[b * BD_ZLD + jr] = (uint16_t)f32_to_bf16_bits(rest);
+    // Z[j][b] fp32 -> hi/lo bf16 tables [b][j - j_lo], zero beyond the range.  The range holds at most
+    // 16 x 32 neurons = 2048 groups of four batch rows: four 16-byte loads per thread, all issued before
+    // the first is used (one load per trip of a loop would put sixteen memory latencies in a row in front
+    // of the stream), and the first pieces of W2 leave right behind them.
+    static_assert(BD_RANGE + 8 <= 16 * 32 && 16 * 32 + 8 <= BD_ZLD && BT_WAVES2 * 64 * 4 >= 16 * 32 * 4, "four groups per thread cover the range");
+    f32x4_b zv[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int u = tid + r * (BT_WAVES2 * 64), jr = u >> 2, qd = u & 3;
+        zv[r] = jr < range ? *(const f32x4_b *)(z + (int64_t)(j_lo + jr) * 16 + qd * 4) : (f32x4_b){0.f, 0.f, 0.f, 0.f};
     }
-    __syncthreads();
 
     const int bq = lane & 15, q = lane >> 4;
     const int c0 = cs * BT_COLS + wave * 64;
@@ -310,10 +311,27 @@ __global__ __launch_bounds__(BT_WAVES2 * 64) void ff_batch_down_kernel(BatchPara
 #pragma unroll
     for (int t = 0; t < 4; ++t)
         acc[t] = (f32x4_b){0.f, 0.f, 0.f, 0.f};
-    if (S > 0) {                 // an empty range (very few neurons) still writes its zero partial
+    if (S > 0) {
 #pragma unroll
-    for (int s = 0; s < BD_DEPTH - 1; ++s)
-        BD_ISSUE(s)
+        for (int s = 0; s < BD_DEPTH - 1; ++s)
+            BD_ISSUE(s)
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int u = tid + r * (BT_WAVES2 * 64), jr = u >> 2, qd = u & 3;
+        if (jr < S * 32) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float v = zv[r][e];
+                const uint32_t h = f32_to_bf16_bits(v);
+                const float rest = v - bf16_bits_to_f32(h);
+                zhi[(qd * 4 + e) * BD_ZLD + jr] = (uint16_t)h;
+                zlo[(qd * 4 + e) * BD_ZLD + jr] = (uint16_t)f32_to_bf16_bits(rest);
+            }
+        }
+    }
+    __syncthreads();
+    if (S > 0) {                 // an empty range (very few neurons) still writes its zero partial
     // LDS reads by inline asm: reads the compiler knows about would wait for every LDS-DMA in flight
     const uint32_t gat = (uint32_t)(q * BD_REGION * 16 + bq * 2);   // row 8q of the slot (region q), column bq of tile 0
     for (int s = 0; s < S; ++s) {
