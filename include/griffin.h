@@ -202,6 +202,25 @@ int griffin_ff_decode_indexed(const griffin_layer *L, const int32_t *idx, int32_
                               size_t workspace_bytes, void *stream);
 
 /*
+ * griffin_ff_decode_indexed for callers that decode many tokens with the same sets (Section 4.2: the
+ * expert neurons are chosen at the prompt and kept for the whole generation phase).  The one-pass
+ * route needs, per neuron, the rows of the batch that selected it; griffin_ff_decode_indexed derives
+ * those membership words from idx at every call, here the caller builds them once:
+ *   sets   griffin_index_sets_bytes(L->n, batch) bytes, device, 4-byte aligned: [ceil(batch/16)][L->n]
+ *          uint32, bit b of word j of group g set iff row 16 g + b holds neuron j; written by
+ *          griffin_index_sets_build(idx, k, batch, L->n, ...), valid as long as idx does not change.
+ * griffin_ff_decode_indexed_sets takes the same idx as well: when the one-pass route does not apply
+ * (fewer than five rows, a workspace sized for k neurons only, a shape it does not cover) the rows
+ * go through the index lists exactly as in griffin_ff_decode_indexed and sets is not read.
+ */
+size_t griffin_index_sets_bytes(int32_t n, int32_t batch);
+int griffin_index_sets_build(const int32_t *idx, int32_t k, int32_t batch, int32_t n, void *sets,
+                             size_t sets_bytes, void *stream);
+int griffin_ff_decode_indexed_sets(const griffin_layer *L, const int32_t *idx, int32_t k, const void *sets,
+                                   int32_t batch, const void *x, void *y, void *workspace,
+                                   size_t workspace_bytes, void *stream);
+
+/*
  * The prompt's own output (Section 5.1: the prompt phase uses the full FF block; Eq. 1):
  *   Y = Z W_2^T + b_2  for the activations Z written by griffin_prefill_select (Z_out).
  *   Z    [total_tokens][d_ff] fp32, row stride ldz elements

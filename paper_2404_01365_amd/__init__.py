@@ -80,6 +80,9 @@ _SIGS = {
     "griffin_ff_decode": (ctypes.c_int, [_LP, _vp, _vp, _i32, _vp, _sz, _vp]),
     "griffin_ff_decode_multi": (ctypes.c_int, [_LP, _i32, _vp, _vp, _vp, _sz, _vp]),
     "griffin_ff_decode_indexed": (ctypes.c_int, [_LP, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
+    "griffin_index_sets_bytes": (_sz, [_i32, _i32]),
+    "griffin_index_sets_build": (ctypes.c_int, [_vp, _i32, _i32, _i32, _vp, _sz, _vp]),
+    "griffin_ff_decode_indexed_sets": (ctypes.c_int, [_LP, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _sz, _vp]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _fn = getattr(lib, _name)
@@ -231,6 +234,22 @@ def griffin_ff_decode_indexed(L: griffin_layer, idx, k: int, batch: int, x, y, *
     _check(lib.griffin_ff_decode_indexed(ctypes.byref(L), _ptr(idx), k, batch, _ptr(x), _ptr(y),
                                          _ptr(workspace), _nbytes(workspace), _stream(stream)),
            "griffin_ff_decode_indexed")
+
+
+def griffin_index_sets_bytes(n: int, batch: int) -> int:
+    return int(lib.griffin_index_sets_bytes(n, batch))
+
+
+def griffin_index_sets_build(idx, k: int, batch: int, n: int, sets, *, stream=None) -> None:
+    _check(lib.griffin_index_sets_build(_ptr(idx), k, batch, n, _ptr(sets), _nbytes(sets), _stream(stream)),
+           "griffin_index_sets_build")
+
+
+def griffin_ff_decode_indexed_sets(L: griffin_layer, idx, k: int, sets, batch: int, x, y, *, workspace,
+                                   stream=None) -> None:
+    _check(lib.griffin_ff_decode_indexed_sets(ctypes.byref(L), _ptr(idx), k, _ptr(sets), batch, _ptr(x), _ptr(y),
+                                              _ptr(workspace), _nbytes(workspace), _stream(stream)),
+           "griffin_ff_decode_indexed_sets")
 
 
 def griffin_prompt_phase_workspace_bytes(L: griffin_layer, total_tokens: int, n_seqs: int) -> int:

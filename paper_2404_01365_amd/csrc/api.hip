@@ -369,7 +369,8 @@ size_t griffin_decode_workspace_bytes(int32_t d, int32_t n, int32_t batch)
 }
 
 static int decode_common(const griffin_layer *L0, const griffin_layer *multi, const int32_t *idx, int32_t k,
-                         int32_t batch, const void *x, void *y, void *ws, size_t ws_bytes, void *stream)
+                         int32_t batch, const void *x, void *y, void *ws, size_t ws_bytes, void *stream,
+                         const uint32_t *sets = nullptr)
 {
     if (batch < 0 || !x || !y)
         return GRIFFIN_EINVAL;
@@ -390,6 +391,7 @@ static int decode_common(const griffin_layer *L0, const griffin_layer *multi, co
     job.W2t = L0->W2t; job.ldt = L0->ldt;
     job.multi = multi;
     job.idx = idx; job.n_src = L0->n;
+    job.sets = sets;
     job.x = x; job.y = y;
     job.part = (float *)ws; job.part_bytes = ws_bytes;
     return launch_decode(job, (hipStream_t)stream);
@@ -435,6 +437,43 @@ int griffin_ff_decode_indexed(const griffin_layer *L, const int32_t *idx, int32_
     if (k < 1 || k > L->n)
         return GRIFFIN_ESHAPE;
     return decode_common(L, nullptr, idx, k, batch, x, y, workspace, workspace_bytes, stream);
+}
+
+size_t griffin_index_sets_bytes(int32_t n, int32_t batch)
+{
+    if (n < 1 || n > MAX_DIM || batch < 1 || batch > GRIFFIN_MAX_BATCH)
+        return 0;
+    return index_sets_words(n, batch) * sizeof(uint32_t);
+}
+
+int griffin_index_sets_build(const int32_t *idx, int32_t k, int32_t batch, int32_t n, void *sets, size_t sets_bytes,
+                             void *stream)
+{
+    if (!idx || !sets || batch < 0)
+        return GRIFFIN_EINVAL;
+    if (batch > GRIFFIN_MAX_BATCH)
+        return GRIFFIN_EUNSUPPORTED;
+    if (n < 1 || n > MAX_DIM || k < 1 || k > n || ((uintptr_t)sets & 3))
+        return GRIFFIN_ESHAPE;
+    if (batch == 0)
+        return GRIFFIN_OK;
+    if (sets_bytes < griffin_index_sets_bytes(n, batch))
+        return GRIFFIN_EWORKSPACE;
+    return launch_index_sets_build(idx, k, batch, n, (uint32_t *)sets, (hipStream_t)stream);
+}
+
+int griffin_ff_decode_indexed_sets(const griffin_layer *L, const int32_t *idx, int32_t k, const void *sets,
+                                   int32_t batch, const void *x, void *y, void *workspace, size_t workspace_bytes,
+                                   void *stream)
+{
+    int rc = check_layer(L);
+    if (rc != GRIFFIN_OK)
+        return rc;
+    if (!idx || !sets)
+        return GRIFFIN_EINVAL;
+    if (k < 1 || k > L->n || ((uintptr_t)sets & 3))
+        return GRIFFIN_ESHAPE;
+    return decode_common(L, nullptr, idx, k, batch, x, y, workspace, workspace_bytes, stream, (const uint32_t *)sets);
 }
 
 }  // extern "C"

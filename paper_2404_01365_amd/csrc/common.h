@@ -151,6 +151,7 @@ struct DecodeJob {
     const griffin_layer *multi;
     const int32_t *idx;      // [batch][n] rows of the full block, or NULL
     int32_t n_src;           // rows in the block idx points into
+    const uint32_t *sets;    // optional membership words of idx, [groups of 16 rows][n_src], built beforehand
     const void *x;
     void *y;
     float *part;
@@ -166,6 +167,8 @@ size_t decode_batch_workspace_floats(int32_t d, int32_t n, int32_t batch);
 size_t decode_masked_workspace_floats(int32_t d, int32_t n_src, int32_t batch);
 int launch_decode_batch_front(const DecodeJob &job, int32_t n_block, const int32_t *idx, int32_t k, int *NR_out,
                               hipStream_t st);
+int launch_index_sets_build(const int32_t *idx, int32_t k, int32_t batch, int32_t n_block, uint32_t *sets, hipStream_t st);
+size_t index_sets_words(int32_t n_block, int32_t batch);
 constexpr int DEC_BATCH_MIN_ROWS = 5;
 int decode_parts(int32_t n, int32_t batch);
 void set_decode_probe(hipEvent_t begin, hipEvent_t mid, hipEvent_t end);

@@ -432,6 +432,25 @@ size_t decode_masked_workspace_floats(int32_t d, int32_t n_src, int32_t batch)
     return decode_batch_workspace_floats(d, n_src, batch) + (size_t)n_src + 64;
 }
 
+// The membership words of every group of 16 rows, [groups][n_block], for callers that build them once
+// per prompt (the sets do not change during generation, Section 4.2).
+int launch_index_sets_build(const int32_t *idx, int32_t k, int32_t batch, int32_t n_block, uint32_t *sets, hipStream_t st)
+{
+    for (int r0 = 0; r0 < batch; r0 += BT_ROWS) {
+        const int rows = batch - r0 < BT_ROWS ? batch - r0 : BT_ROWS;
+        uint32_t *mask = sets + (size_t)(r0 / BT_ROWS) * n_block;
+        hipLaunchKernelGGL(batch_mask_zero_kernel, dim3((n_block + 255) / 256), dim3(256), 0, st, mask, n_block);
+        hipLaunchKernelGGL(batch_mask_build_kernel, dim3((k + 255) / 256, rows), dim3(256), 0, st,
+                           idx + (int64_t)r0 * k, rows, k, n_block, mask);
+    }
+    return check_launch("batch_mask_build_kernel");
+}
+
+size_t index_sets_words(int32_t n_block, int32_t batch)
+{
+    return (size_t)((batch + BT_ROWS - 1) / BT_ROWS) * n_block;
+}
+
 // Runs both kernels for every group of up to 16 rows; leaves part[b][NR][d] for the reduce kernel.
 // n_block neurons in the block; idx (or NULL) [batch][k]: the rows' own sets inside that block.
 int launch_decode_batch_front(const DecodeJob &job, int32_t n_block, const int32_t *idx, int32_t k, int *NR_out,
@@ -481,7 +500,9 @@ int launch_decode_batch_front(const DecodeJob &job, int32_t n_block, const int32
         p.rows = job.batch - r0 < BT_ROWS ? job.batch - r0 : BT_ROWS;
         p.x = (const uint16_t *)job.x + (int64_t)r0 * job.d;
         p.part = job.part + (size_t)r0 * NR * job.d;
-        if (idx) {
+        if (job.sets) {
+            p.mask = job.sets + (size_t)(r0 / BT_ROWS) * n_block;      // built once per prompt by the caller
+        } else if (idx) {
             hipLaunchKernelGGL(batch_mask_zero_kernel, dim3((n_block + 255) / 256), dim3(256), 0, st, mask, n_block);
             hipLaunchKernelGGL(batch_mask_build_kernel, dim3((k + 255) / 256, p.rows), dim3(256), 0, st,
                                idx + (int64_t)r0 * k, p.rows, k, n_block, mask);

@@ -182,6 +182,30 @@ def test_prompt_phase_rejects_bad_arguments_without_hip():
     assert G.griffin_prompt_phase_workspace_bytes(mk(d=250), 512, 1) == 0
 
 
+def test_index_sets_reject_bad_arguments_without_hip():
+    lib = G.lib
+    assert G.griffin_index_sets_bytes(14336, 16) == 14336 * 4
+    assert G.griffin_index_sets_bytes(14336, 17) == 2 * 14336 * 4        # one word per neuron and group of 16 rows
+    assert G.griffin_index_sets_bytes(0, 16) == 0 and G.griffin_index_sets_bytes(100, G.MAX_BATCH + 1) == 0
+    big = 1 << 30
+    # idx, k, batch, n, sets, sets_bytes, stream
+    assert lib.griffin_index_sets_build(None, 10, 4, 100, FAKE, big, None) == G.EINVAL
+    assert lib.griffin_index_sets_build(FAKE, 10, 4, 100, None, big, None) == G.EINVAL
+    assert lib.griffin_index_sets_build(FAKE, 101, 4, 100, FAKE, big, None) == G.ESHAPE
+    assert lib.griffin_index_sets_build(FAKE, 10, 4, 100, FAKE + 2, big, None) == G.ESHAPE
+    assert lib.griffin_index_sets_build(FAKE, 10, 4, 100, FAKE, 399, None) == G.EWORKSPACE
+    assert lib.griffin_index_sets_build(FAKE, 10, G.MAX_BATCH + 1, 100, FAKE, big, None) == G.EUNSUPPORTED
+    assert lib.griffin_index_sets_build(FAKE, 10, 0, 100, FAKE, 0, None) == G.OK
+    L = mk(d=512, n=688, dtype=G.BF16)
+    # L, idx, k, sets, batch, x, y, ws, ws_bytes, stream
+    ds = lib.griffin_ff_decode_indexed_sets
+    assert ds(ctypes.byref(L), None, 10, FAKE, 8, FAKE, FAKE, FAKE, big, None) == G.EINVAL
+    assert ds(ctypes.byref(L), FAKE, 10, None, 8, FAKE, FAKE, FAKE, big, None) == G.EINVAL
+    assert ds(ctypes.byref(L), FAKE, 689, FAKE, 8, FAKE, FAKE, FAKE, big, None) == G.ESHAPE
+    assert ds(ctypes.byref(L), FAKE, 10, FAKE, 8, FAKE, FAKE, None, 0, None) == G.EWORKSPACE
+    assert ds(ctypes.byref(L), FAKE, 10, FAKE, 0, FAKE, FAKE, FAKE, big, None) == G.OK
+
+
 def test_batch_decode_workspace_covers_the_matrix_core_path():
     # 16 rows through one block: partial rows [16][ranges][d] plus the table of Z [n][16]
     d, n = 4096, 5504

@@ -175,6 +175,40 @@ def test_decode_through_transposed_w2_reuses_a_workspace_with_anything_in_it():
             assert max_rel(to_host(ys[step]), ref) <= TOL_OUT[dtype], (fill, step)
 
 
+@pytest.mark.parametrize("d,n,k,B", [(1024, 700, 300, 19), (512, 9000, 150, 6), (1024, 300, 100, 3)])
+def test_indexed_decode_with_sets_built_once(d, n, k, B):
+    """The membership words built once per prompt (the sets stay fixed during generation, Section 4.2)
+    give, token after token, bit for bit what griffin_ff_decode_indexed gives, and the oracle's result;
+    with fewer than five rows the index lists are used and the words are not read."""
+    dtype, act = synth.DT_BF16, synth.ACT_SILU
+    T = 3
+    c = synth.small_case(d + n + B, d, n, 4, dtype, T=B * T)
+    L, _ = dev_layer(c["Wg"], c["W1"], c["W2"], act, dtype)
+    rng = np.random.default_rng(B)
+    idx = np.stack([np.sort(rng.choice(n, k, replace=False)) for _ in range(B)]).astype(np.int32)
+    idx_dev = torch.from_numpy(idx).cuda()
+    sets = torch.full((G.griffin_index_sets_bytes(n, B) // 4,), -1, dtype=torch.int32, device="cuda")
+    G.griffin_index_sets_build(idx_dev, k, B, n, sets)
+    sync()
+    # the words themselves: bit b of word j of group g <=> neuron j in the set of row 16 g + b
+    words = sets.cpu().numpy().view(np.uint32).reshape(-1, n)
+    want = np.zeros_like(words)
+    for b in range(B):
+        want[b // 16, idx[b]] |= np.uint32(1 << (b % 16))
+    assert np.array_equal(words, want)
+    ws = workspace(G.griffin_decode_workspace_bytes(d, n, B))
+    for t in range(T):
+        x = to_dev(c["xt"][t * B:(t + 1) * B], dtype)
+        y1, y2 = torch.empty_like(x), torch.empty_like(x)
+        G.griffin_ff_decode_indexed_sets(L, idx_dev, k, sets, B, x, y1, workspace=ws)
+        G.griffin_ff_decode_indexed(L, idx_dev, k, B, x, y2, workspace=ws)
+        sync()
+        assert np.array_equal(to_host(y1), to_host(y2)), t
+        for b in range(0, B, 4):
+            ref = oracle.ff_decode(c["xt"][t * B + b], c["Wg"][idx[b]], c["W1"][idx[b]], c["W2"][idx[b]], act)
+            assert max_rel(to_host(y1)[b], ref) <= TOL_OUT[dtype], (t, b)
+
+
 # ------------------------------------------------------------------ compaction
 @pytest.mark.parametrize("interleaved", [False, True])
 @pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
