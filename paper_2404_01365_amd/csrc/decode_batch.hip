@@ -413,7 +413,8 @@ bool decode_batch_supported(int32_t d, int32_t n, bool bf16)
 int decode_batch_ranges(int32_t d, int32_t n)
 {
     const int CS = d / BT_COLS;
-    int NR = (256 + CS - 1) / CS;              // enough workgroups for every CU
+    int NR = 256 / CS;                         // as many workgroups as fit the chip at once: one more than the CUs
+                                               // (d = 3072: 43 x 6 = 258) and the stragglers double the kernel's time
     if (NR > 64) NR = 64;
     const int by_range = (n + BD_RANGE - 1) / BD_RANGE;
     if (NR < by_range) NR = by_range;          // a workgroup's range of Z must fit its LDS tables
