@@ -115,6 +115,7 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
                                                     int tile_n)
 {
     constexpr int BM = 64 * MI;
+    constexpr bool WIDE = PLAIN && GATED;     // plain product over a 256-column tile: accG = columns n0 + 128 ..
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1, l31 = lane & 31, lh = lane >> 5;
     const bool vec = ((p.F | (int32_t)p.ldz) & 3) == 0 && ((uintptr_t)p.Z & 15) == 0;
@@ -131,7 +132,11 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
         const uint32_t patch = patch_lds + (uint32_t)(wave * 32 * 256);
         const uint32_t wr = patch + (uint32_t)(l31 * 256);
         const int rrow = lane >> 4, rch = lane & 15;
-        const int ncol = n0 + wn * 64 + rch * 4;
+        // (the plain product's wide tile: the second set of accumulators holds the columns 128 further on)
+#pragma unroll
+        for (int half = 0; half < (WIDE ? 2 : 1); ++half) {
+        const int nh = n0 + half * G_BN;
+        const int ncol = nh + wn * 64 + rch * 4;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
             const int lrow = wm * (32 * MI) + mi * 32 + l31;
@@ -143,10 +148,10 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
                     f32x4_t v;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float u = ff1_acc_read(accU[mi][ni][g * 4 + e]);
+                        const float u = ff1_acc_read(half == 0 ? accU[mi][ni][g * 4 + e] : accG[mi][ni][g * 4 + e]);
                         v[e] = PLAIN ? u : (GATED ? act_apply_t<ACT>(ff1_acc_read(accG[mi][ni][g * 4 + e])) * u : act_apply_t<ACT>(u));
                     }
-                    if (n0 + wn * 64 + ni * 32 + g * 8 + lh * 4 >= p.F)
+                    if (nh + wn * 64 + ni * 32 + g * 8 + lh * 4 >= p.F)
                         v = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
                     sq = fmaf(v[0], v[0], sq); sq = fmaf(v[1], v[1], sq);
                     sq = fmaf(v[2], v[2], sq); sq = fmaf(v[3], v[3], sq);
@@ -187,6 +192,7 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
             FF1_PATCH_STORE(0) FF1_PATCH_STORE(1) FF1_PATCH_STORE(2) FF1_PATCH_STORE(3)
             FF1_PATCH_STORE(4) FF1_PATCH_STORE(5) FF1_PATCH_STORE(6) FF1_PATCH_STORE(7)
 #undef FF1_PATCH_STORE
+        }
         }
         if (PLAIN)
             return true;
@@ -231,6 +237,8 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
                     if (rowok)
                         zrow[col] = z;
                 }
+                if (WIDE && col + G_BN < p.F && rowok)
+                    zrow[col + G_BN] = gt;
             }
         }
         rs[wn * 2 + lh][lrow] = sq;
@@ -275,6 +283,11 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
     constexpr int XQ = BM / 32, WQ = G_BN / 32;                // 8-row regions per wave per k-tile
     constexpr int NLOADS = XQ + (GATED ? 2 : 1) * WQ;          // LDS-DMA instructions per wave per k-tile
     constexpr int H1 = NLOADS / 2;
+    // The plain product has one B matrix: its tile is 256 columns wide and the "gate" half of the
+    // machinery (LDS section, fragments, accumulators) takes columns n0 + 128 .. n0 + 255, which
+    // halves the X traffic per flop exactly as the dual product does.
+    constexpr bool WIDE = PLAIN && GATED;
+    constexpr int TILE_N = WIDE ? 2 * G_BN : G_BN;
     __shared__ u32x4 lds[2 * STAGE];
     __shared__ float rs[4][BM];
 
@@ -302,26 +315,31 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
     const int lrow = lane >> 3;
     int m0, n0, tile_n, kt0, KT;
     float *Zt;
-    uint32_t xvo[XQ], wvo[WQ];
+    uint32_t xvo[XQ], wvo[WQ], wgvo[WQ];
     __amdgpu_buffer_rsrc_t rX, rW1, rWg;
 #define FF1_TILE_ADDR(logical_)                                                                          \
     {                                                                                                    \
         const int split_ = (logical_) / ntile, tile_ = (logical_) % ntile;                               \
         tile_n = tile_ / p.mt;                                                                           \
         m0 = (tile_ % p.mt) * BM;                                                                        \
-        n0 = tile_n * G_BN;                                                                              \
+        n0 = tile_n * TILE_N;                                                                            \
         Zt = PLAIN ? p.Z + (int64_t)split_ * p.M * p.ldz : p.Z;                                          \
         _Pragma("unroll") for (int q = 0; q < XQ; ++q)                                                   \
             xvo[q] = (uint32_t)min((wave * XQ + q) * 8 + lrow, p.M - 1 - m0) * (uint32_t)(p.ldx * 2) +   \
                      (uint32_t)(((lane & 7) ^ FF1_SWZ((wave * XQ + q) * 8 + lrow)) * 16);                \
         _Pragma("unroll") for (int q = 0; q < WQ; ++q)                                                   \
+        {                                                                                                \
             wvo[q] = (uint32_t)min((wave * WQ + q) * 8 + lrow, p.F - 1 - n0) * (uint32_t)(p.ldw * 2) +   \
                      (uint32_t)(((lane & 7) ^ FF1_SWZ((wave * WQ + q) * 8 + lrow)) * 16);                \
+            wgvo[q] = WIDE ? (uint32_t)min(G_BN + (wave * WQ + q) * 8 + lrow, p.F - 1 - n0) * (uint32_t)(p.ldw * 2) + \
+                             (uint32_t)(((lane & 7) ^ FF1_SWZ((wave * WQ + q) * 8 + lrow)) * 16)         \
+                           : wvo[q];                                                                     \
+        }                                                                                                \
         rX = __builtin_amdgcn_make_buffer_rsrc((void *)((const uint16_t *)p.X + (int64_t)m0 * p.ldx), 0, \
                                                RSRC_RECORDS, RSRC_FLAGS);                                \
         rW1 = __builtin_amdgcn_make_buffer_rsrc((void *)((const uint16_t *)p.W1 + (int64_t)n0 * p.ldw), 0, \
                                                 RSRC_RECORDS, RSRC_FLAGS);                               \
-        rWg = __builtin_amdgcn_make_buffer_rsrc((void *)((const uint16_t *)(GATED ? p.Wg : p.W1) + (int64_t)n0 * p.ldw), 0, \
+        rWg = __builtin_amdgcn_make_buffer_rsrc((void *)((const uint16_t *)((GATED && !PLAIN) ? p.Wg : p.W1) + (int64_t)n0 * p.ldw), 0, \
                                                 RSRC_RECORDS, RSRC_FLAGS);                               \
         kt0 = split_ * p.kt_per_split;                                                                   \
         KT = min(p.kt_per_split, p.d / BK - kt0);      /* k-tiles of this range (>= 1 by construction) */ \
@@ -343,7 +361,7 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
                                                      wvo[((q) - XQ) % WQ], so_, 0, 2);                   \
         else if (GATED)                                                                                  \
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rWg, (lds_void_t *)(st_ + WG_SLOT + (wave * WQ + ((q) - XQ) % WQ) * 64), 16, \
-                                                     wvo[((q) - XQ) % WQ], so_, 0, 2);                   \
+                                                     wgvo[((q) - XQ) % WQ], so_, 0, 2);                  \
     }
 // Operand fragments are fetched with ds_read_b128 written as inline asm: the compiler makes every
 // LDS load it knows about wait for ALL LDS-DMA in flight (it cannot tell the stages apart), which
@@ -430,7 +448,7 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
     // wholly inside the matrix (8 per 32-token block, plus the row sums when all four waves write them).
     // The wait for k-tile 0 of the next tile may leave that many operations outstanding, no more: a
     // wave that issued fewer stores than the wait allows would sail through before its loads landed.
-    constexpr int EPI_STORES = MI * 8 + ((!PLAIN && MI == 4) ? 1 : 0);
+    constexpr int EPI_STORES = MI * 8 * (WIDE ? 2 : 1) + ((!PLAIN && MI == 4) ? 1 : 0);
     const uint32_t rs_lds = (uint32_t)(uintptr_t)(lds_void_t *)rs;
     const uint32_t patch_lds = lds0 + (uint32_t)(STAGE * 16) + (GATED ? (uint32_t)(BM * 128) : 0u);
 #define FF1_FIRST_LOADS()                                                                      \
@@ -452,7 +470,7 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
         if (stores_known && !PLAIN && p.Zb)      // twice the Z stores: more than the counter holds, 63 is as good
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(H1 + EPI_STORES + MI * 8 > 63 ? 63 : H1 + EPI_STORES + MI * 8));
         else if (stores_known)
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(H1 + EPI_STORES));
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(H1 + EPI_STORES > 63 ? 63 : H1 + EPI_STORES));
         else
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(H1));
         FF1_BARRIER()
@@ -493,7 +511,7 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
         Ff1Params pt = p;
         pt.Z = Zt;
         const int m0c = m0, n0c = n0, tile_nc = tile_n;
-        const bool whole = m0 + BM <= p.M && n0 + G_BN <= p.F;
+        const bool whole = m0 + BM <= p.M && n0 + TILE_N <= p.F;
         slot += wg_per_xcd;
         const int logical_n = (int)(blockIdx.x & 7) * per_xcd + slot;
         const bool more = slot < per_xcd && logical_n < nblk;
@@ -856,7 +874,7 @@ bool gemm_nt_partials_ok(int64_t M, int32_t N, int32_t K, int64_t lda, int64_t l
 void gemm_nt_split_plan(int64_t M, int32_t N, int32_t K, int *splits, int *kt_per_split)
 {
     const int bm = M > 128 ? 256 : 128;
-    const int64_t ntile = ((M + bm - 1) / bm) * ((N + G_BN - 1) / G_BN);
+    const int64_t ntile = ((M + bm - 1) / bm) * ((N + 2 * G_BN - 1) / (2 * G_BN));
     const int KT = K / 64;
     int best = 1;
     int64_t best_cost = -1;
@@ -866,7 +884,10 @@ void gemm_nt_split_plan(int64_t M, int32_t N, int32_t K, int *splits, int *kt_pe
             break;
         const int used = (KT + per - 1) / per;
         const int64_t rounds = (ntile * used + 255) / 256;
-        const int64_t cost = rounds * (per + 8);           // 8 k-tiles' worth of prologue and epilogue per item
+        // in units of one k-tile on every CU (~1.1 us): 8 k-tiles' worth of prologue and epilogue per item, and
+        // every range writes an fp32 slab that the sum reads again (8 bytes per element at ~5 TB/s: 5.4 MB per unit)
+        const int64_t slab = (int64_t)used * ((M * N * 8) / 5400000);
+        const int64_t cost = rounds * (per + 8) + slab;
         if (best_cost < 0 || cost < best_cost) {
             best_cost = cost;
             best = s;
@@ -887,15 +908,15 @@ int launch_gemm_nt_partials(const void *A, int64_t lda, const void *B, int64_t l
     p.ldx = lda; p.ldw = ldb; p.ldz = N;
     p.M = (int32_t)M; p.F = N; p.d = K;
     p.splits = splits; p.kt_per_split = kt_per_split;
-    p.nt = (N + G_BN - 1) / G_BN;
+    p.nt = (N + 2 * G_BN - 1) / (2 * G_BN);        // 256-column tiles: both sets of accumulators hold columns of B
     if (M > 128) {
         p.mt = (int32_t)((M + 255) / 256);
         const int nblk = p.mt * p.nt * splits;
-        hipLaunchKernelGGL((ff1_bf16_mfma_kernel<GRIFFIN_ACT_RELU, false, 4, true>), dim3(ff1_grid(nblk)), dim3(G_THREADS), 0, st, p);
+        hipLaunchKernelGGL((ff1_bf16_mfma_kernel<GRIFFIN_ACT_RELU, true, 4, true>), dim3(ff1_grid(nblk)), dim3(G_THREADS), 0, st, p);
     } else {
         p.mt = (int32_t)((M + 127) / 128);
         const int nblk = p.mt * p.nt * splits;
-        hipLaunchKernelGGL((ff1_bf16_mfma_kernel<GRIFFIN_ACT_RELU, false, 2, true>), dim3(ff1_grid(nblk)), dim3(G_THREADS), 0, st, p);
+        hipLaunchKernelGGL((ff1_bf16_mfma_kernel<GRIFFIN_ACT_RELU, true, 2, true>), dim3(ff1_grid(nblk)), dim3(G_THREADS), 0, st, p);
     }
     return check_launch("ff1_bf16_mfma_kernel");
 }
