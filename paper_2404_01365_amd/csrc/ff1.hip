@@ -121,8 +121,9 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
     const bool vec = ((p.F | (int32_t)p.ldz) & 3) == 0 && ((uintptr_t)p.Z & 15) == 0;
     const bool hb = !PLAIN && (p.b1 != nullptr || (GATED && p.bg != nullptr));
     const uint16_t *b1p = (const uint16_t *)p.b1, *bgp = (const uint16_t *)p.bg;
-    if (vec && !hb) {
-        // The usual case (no biases, 16-byte aligned rows of Z, F a multiple of 4).  A wave's
+    const bool bias8 = (((uintptr_t)p.b1 | (uintptr_t)p.bg) & 7) == 0;       // four biases per 8-byte load
+    if (vec && (!hb || bias8)) {
+        // The usual case (16-byte aligned rows of Z, F a multiple of 4).  A wave's
         // 32-token x 64-neuron block goes through a private LDS patch (32 rows of 256 B, 16-byte
         // chunk c of row r at c ^ (r & 15): writes and reads both spread evenly over the banks) and
         // leaves as 16-byte stores that cover four whole 256-byte row pieces per instruction;
@@ -132,6 +133,17 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
         const uint32_t patch = patch_lds + (uint32_t)(wave * 32 * 256);
         const uint32_t wr = patch + (uint32_t)(l31 * 256);
         const int rrow = lane >> 4, rch = lane & 15;
+        // biases of this lane's 32 columns (four consecutive ones per register pair), fetched before any store
+        // of Z leaves: a load behind the stores would wait for them all
+        uint2 b1w[2][4], bgw[2][4];
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int c = min(n0 + wn * 64 + ni * 32 + g * 8 + lh * 4, p.F - 4);
+                b1w[ni][g] = (hb && b1p) ? *(const uint2 *)(b1p + c) : make_uint2(0u, 0u);
+                bgw[ni][g] = (hb && GATED && bgp) ? *(const uint2 *)(bgp + c) : make_uint2(0u, 0u);
+            }
         // (the plain product's wide tile: the second set of accumulators holds the columns 128 further on)
 #pragma unroll
         for (int half = 0; half < (WIDE ? 2 : 1); ++half) {
@@ -148,8 +160,15 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
                     f32x4_t v;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float u = ff1_acc_read(half == 0 ? accU[mi][ni][g * 4 + e] : accG[mi][ni][g * 4 + e]);
-                        v[e] = PLAIN ? u : (GATED ? act_apply_t<ACT>(ff1_acc_read(accG[mi][ni][g * 4 + e])) * u : act_apply_t<ACT>(u));
+                        float u = ff1_acc_read(half == 0 ? accU[mi][ni][g * 4 + e] : accG[mi][ni][g * 4 + e]);
+                        float gt = (GATED && !PLAIN) ? ff1_acc_read(accG[mi][ni][g * 4 + e]) : 0.0f;
+                        if (hb) {
+                            const uint32_t wu = e < 2 ? b1w[ni][g].x : b1w[ni][g].y, wg2 = e < 2 ? bgw[ni][g].x : bgw[ni][g].y;
+                            u += __uint_as_float((e & 1) ? (wu & 0xFFFF0000u) : (wu << 16));
+                            if (GATED)
+                                gt += __uint_as_float((e & 1) ? (wg2 & 0xFFFF0000u) : (wg2 << 16));
+                        }
+                        v[e] = PLAIN ? u : (GATED ? act_apply_t<ACT>(gt) * u : act_apply_t<ACT>(u));
                     }
                     if (nh + wn * 64 + ni * 32 + g * 8 + lh * 4 >= p.F)
                         v = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
@@ -818,12 +837,13 @@ static void launch_mfma_act(const Ff1Params &p, int act, bool gated, hipStream_t
 }
 
 // Will the first GEMM's own epilogue leave a bf16 copy of Z beside the fp32 one?  Only the direct-to-LDS
-// kernel's usual store path does (bf16 block, d in whole k-tiles, no biases, 16-byte aligned rows of Z).
+// kernel's usual store path does (bf16 block, d in whole k-tiles, 16-byte aligned rows of Z, biases 8-byte aligned).
 bool ff1_can_write_zb(const griffin_layer &L, int64_t ldx, const float *Z, int64_t ldz)
 {
     const bool ktail = L.d % 64 != 0 || ldx > (1 << 21) || L.ld > (1 << 21);
     const bool vec = ((L.n | (int32_t)ldz) & 3) == 0 && ((uintptr_t)Z & 15) == 0;
-    return L.dtype == GRIFFIN_BF16 && !ktail && vec && !L.b1 && !L.bg;
+    const bool bias8 = (((uintptr_t)L.b1 | (uintptr_t)L.bg) & 7) == 0;
+    return L.dtype == GRIFFIN_BF16 && !ktail && vec && bias8;
 }
 
 int launch_ff1(const griffin_layer &L, const void *X, int64_t ldx, int64_t M, float *Z, int64_t ldz,
