@@ -109,17 +109,19 @@ __device__ __forceinline__ float ff1_acc_read(float a)
     return v;
 }
 
-template <int ACT, bool GATED, int MI, bool PLAIN>
+template <int ACT, bool GATED, int MI, bool PLAIN, bool EQ2W = false>
 __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (&accU)[MI][2], f32x16 (&accG)[MI][2],
                                                     float (*rs)[64 * MI], uint32_t rs_lds, uint32_t patch_lds, int m0, int n0,
                                                     int tile_n)
 {
     constexpr int BM = 64 * MI;
-    constexpr bool WIDE = PLAIN && GATED;     // plain product over a 256-column tile: accG = columns n0 + 128 ..
+    // one B matrix (the plain product, or an Eq. 2 block) over a 256-column tile: accG = columns n0 + 128 ..
+    constexpr bool WIDE = (PLAIN && GATED) || EQ2W;
+    constexpr bool GLU = GATED && !PLAIN && !EQ2W;          // accG is the gate (Eq. 3)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1, l31 = lane & 31, lh = lane >> 5;
     const bool vec = ((p.F | (int32_t)p.ldz) & 3) == 0 && ((uintptr_t)p.Z & 15) == 0;
-    const bool hb = !PLAIN && (p.b1 != nullptr || (GATED && p.bg != nullptr));
+    const bool hb = !PLAIN && (p.b1 != nullptr || (GLU && p.bg != nullptr));
     const uint16_t *b1p = (const uint16_t *)p.b1, *bgp = (const uint16_t *)p.bg;
     const bool bias8 = (((uintptr_t)p.b1 | (uintptr_t)p.bg) & 7) == 0;       // four biases per 8-byte load
     if (vec && (!hb || bias8)) {
@@ -142,17 +144,20 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
             for (int g = 0; g < 4; ++g) {
                 const int c = min(n0 + wn * 64 + ni * 32 + g * 8 + lh * 4, p.F - 4);
                 b1w[ni][g] = (hb && b1p) ? *(const uint2 *)(b1p + c) : make_uint2(0u, 0u);
-                bgw[ni][g] = (hb && GATED && bgp) ? *(const uint2 *)(bgp + c) : make_uint2(0u, 0u);
+                if (EQ2W)       // the second half's b1, 128 columns further on
+                    bgw[ni][g] = (hb && b1p) ? *(const uint2 *)(b1p + min(c + G_BN, p.F - 4)) : make_uint2(0u, 0u);
+                else
+                    bgw[ni][g] = (hb && GLU && bgp) ? *(const uint2 *)(bgp + c) : make_uint2(0u, 0u);
             }
         // (the plain product's wide tile: the second set of accumulators holds the columns 128 further on)
-#pragma unroll
-        for (int half = 0; half < (WIDE ? 2 : 1); ++half) {
-        const int nh = n0 + half * G_BN;
-        const int ncol = nh + wn * 64 + rch * 4;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
             const int lrow = wm * (32 * MI) + mi * 32 + l31;
             float sq = 0.0f;
+#pragma unroll
+        for (int half = 0; half < (WIDE ? 2 : 1); ++half) {
+        const int nh = n0 + half * G_BN;
+        const int ncol = nh + wn * 64 + rch * 4;
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni) {
 #pragma unroll
@@ -161,14 +166,15 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         float u = ff1_acc_read(half == 0 ? accU[mi][ni][g * 4 + e] : accG[mi][ni][g * 4 + e]);
-                        float gt = (GATED && !PLAIN) ? ff1_acc_read(accG[mi][ni][g * 4 + e]) : 0.0f;
+                        float gt = GLU ? ff1_acc_read(accG[mi][ni][g * 4 + e]) : 0.0f;
                         if (hb) {
-                            const uint32_t wu = e < 2 ? b1w[ni][g].x : b1w[ni][g].y, wg2 = e < 2 ? bgw[ni][g].x : bgw[ni][g].y;
+                            const uint2 &bu = (EQ2W && half == 1) ? bgw[ni][g] : b1w[ni][g];
+                            const uint32_t wu = e < 2 ? bu.x : bu.y, wg2 = e < 2 ? bgw[ni][g].x : bgw[ni][g].y;
                             u += __uint_as_float((e & 1) ? (wu & 0xFFFF0000u) : (wu << 16));
-                            if (GATED)
+                            if (GLU)
                                 gt += __uint_as_float((e & 1) ? (wg2 & 0xFFFF0000u) : (wg2 << 16));
                         }
-                        v[e] = PLAIN ? u : (GATED ? act_apply_t<ACT>(gt) * u : act_apply_t<ACT>(u));
+                        v[e] = PLAIN ? u : (GLU ? act_apply_t<ACT>(gt) * u : act_apply_t<ACT>(u));
                     }
                     if (nh + wn * 64 + ni * 32 + g * 8 + lh * 4 >= p.F)
                         v = (f32x4_t){0.0f, 0.0f, 0.0f, 0.0f};
@@ -181,8 +187,6 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            if (!PLAIN)
-                asm volatile("ds_write_b32 %0, %1" :: "v"(rs_lds + (uint32_t)(((wn * 2 + lh) * BM + lrow) * 4)), "v"(sq) : "memory");
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             // rows 4j + rrow of the patch, 16 bytes per lane
             const int tok0 = m0 + wm * (32 * MI) + mi * 32 + rrow;
@@ -212,6 +216,8 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
             FF1_PATCH_STORE(4) FF1_PATCH_STORE(5) FF1_PATCH_STORE(6) FF1_PATCH_STORE(7)
 #undef FF1_PATCH_STORE
         }
+            if (!PLAIN)     // the row's sum of squares over all the columns of the tile (both halves)
+                asm volatile("ds_write_b32 %0, %1" :: "v"(rs_lds + (uint32_t)(((wn * 2 + lh) * BM + lrow) * 4)), "v"(sq) : "memory");
         }
         if (PLAIN)
             return true;
@@ -249,15 +255,20 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
                 float u = ff1_acc_read(accU[mi][ni][i]);
                 float gt = GATED ? ff1_acc_read(accG[mi][ni][i]) : 0.0f;
                 if (!PLAIN && b1p) u += bf16_bits_to_f32(b1p[cj]);
-                if (!PLAIN && GATED && bgp) gt += bf16_bits_to_f32(bgp[cj]);
-                const float z = PLAIN ? u : (GATED ? act_apply_t<ACT>(gt) * u : act_apply_t<ACT>(u));
+                if (GLU && bgp) gt += bf16_bits_to_f32(bgp[cj]);
+                if (EQ2W && b1p) gt += bf16_bits_to_f32(b1p[min(col + G_BN, p.F - 1)]);
+                const float z = PLAIN ? u : (GLU ? act_apply_t<ACT>(gt) * u : act_apply_t<ACT>(u));
                 if (col < p.F) {
                     sq = fmaf(z, z, sq);
                     if (rowok)
                         zrow[col] = z;
                 }
-                if (WIDE && col + G_BN < p.F && rowok)
-                    zrow[col + G_BN] = gt;
+                if (WIDE && col + G_BN < p.F) {
+                    const float z2 = EQ2W ? act_apply_t<ACT>(gt) : gt;
+                    sq = fmaf(z2, z2, sq);
+                    if (rowok)
+                        zrow[col + G_BN] = z2;
+                }
             }
         }
         rs[wn * 2 + lh][lrow] = sq;
@@ -292,7 +303,7 @@ typedef __attribute__((address_space(3))) void lds_void_t;
 // slot swizzle of row r (rows of every stage section start at a multiple of 16)
 #define FF1_SWZ(r) (((r) >> 1) & 7)
 
-template <int ACT, bool GATED, int MI, bool PLAIN>
+template <int ACT, bool GATED, int MI, bool PLAIN, bool EQ2W = false>
 __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass has no buffer-descriptor builtins; it only needs the launch stub
@@ -305,7 +316,8 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
     // The plain product has one B matrix: its tile is 256 columns wide and the "gate" half of the
     // machinery (LDS section, fragments, accumulators) takes columns n0 + 128 .. n0 + 255, which
     // halves the X traffic per flop exactly as the dual product does.
-    constexpr bool WIDE = PLAIN && GATED;
+    constexpr bool WIDE = (PLAIN && GATED) || EQ2W;        // EQ2W: an Eq. 2 block (no gate) through the same machinery
+    static_assert(!EQ2W || (GATED && !PLAIN), "the Eq. 2 wide tile uses both LDS sections and both accumulator sets");
     constexpr int TILE_N = WIDE ? 2 * G_BN : G_BN;
     __shared__ u32x4 lds[2 * STAGE];
     __shared__ float rs[4][BM];
@@ -358,7 +370,7 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
                                                RSRC_RECORDS, RSRC_FLAGS);                                \
         rW1 = __builtin_amdgcn_make_buffer_rsrc((void *)((const uint16_t *)p.W1 + (int64_t)n0 * p.ldw), 0, \
                                                 RSRC_RECORDS, RSRC_FLAGS);                               \
-        rWg = __builtin_amdgcn_make_buffer_rsrc((void *)((const uint16_t *)((GATED && !PLAIN) ? p.Wg : p.W1) + (int64_t)n0 * p.ldw), 0, \
+        rWg = __builtin_amdgcn_make_buffer_rsrc((void *)((const uint16_t *)((GATED && !PLAIN && !EQ2W) ? p.Wg : p.W1) + (int64_t)n0 * p.ldw), 0, \
                                                 RSRC_RECORDS, RSRC_FLAGS);                               \
         kt0 = split_ * p.kt_per_split;                                                                   \
         KT = min(p.kt_per_split, p.d / BK - kt0);      /* k-tiles of this range (>= 1 by construction) */ \
@@ -538,7 +550,7 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
             FF1_TILE_ADDR(logical_n)
             FF1_FIRST_LOADS()
         }
-        const bool usual = ff1_mfma_epilogue_t<ACT, GATED, MI, PLAIN>(pt, accU, accG, rs, rs_lds, patch_lds, m0c, n0c, tile_nc);
+        const bool usual = ff1_mfma_epilogue_t<ACT, GATED, MI, PLAIN, EQ2W>(pt, accU, accG, rs, rs_lds, patch_lds, m0c, n0c, tile_nc);
         if (!more)
             break;
         FF1_BARRIER()              // every wave is done with its patch and the row sums
@@ -810,7 +822,7 @@ static int ff1_grid(int nblk)
 }
 
 template <int ACT, int MI>
-static void launch_mfma(const Ff1Params &p, bool gated, hipStream_t st)
+static void launch_mfma(const Ff1Params &p, bool gated, bool wide, hipStream_t st)
 {
     const int nblk = p.mt * p.nt;
     dim3 grid(ff1_grid(nblk)), block(G_THREADS);
@@ -822,17 +834,18 @@ static void launch_mfma(const Ff1Params &p, bool gated, hipStream_t st)
         else hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, true, MI, false>), grid, block, 0, st, p);
     } else {
         if (ktail) hipLaunchKernelGGL((ff1_bf16_mfma_staged_kernel<ACT, false, MI, true>), grid_all, block, 0, st, p);
+        else if (wide) hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, true, MI, false, true>), grid, block, 0, st, p);   // 256-column tiles
         else hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, false, MI, false>), grid, block, 0, st, p);
     }
 }
 
 template <int MI>
-static void launch_mfma_act(const Ff1Params &p, int act, bool gated, hipStream_t st)
+static void launch_mfma_act(const Ff1Params &p, int act, bool gated, bool wide, hipStream_t st)
 {
     switch (act) {
-    case GRIFFIN_ACT_SILU: launch_mfma<GRIFFIN_ACT_SILU, MI>(p, gated, st); break;
-    case GRIFFIN_ACT_GELU_TANH: launch_mfma<GRIFFIN_ACT_GELU_TANH, MI>(p, gated, st); break;
-    default: launch_mfma<GRIFFIN_ACT_RELU, MI>(p, gated, st); break;
+    case GRIFFIN_ACT_SILU: launch_mfma<GRIFFIN_ACT_SILU, MI>(p, gated, wide, st); break;
+    case GRIFFIN_ACT_GELU_TANH: launch_mfma<GRIFFIN_ACT_GELU_TANH, MI>(p, gated, wide, st); break;
+    default: launch_mfma<GRIFFIN_ACT_RELU, MI>(p, gated, wide, st); break;
     }
 }
 
@@ -858,18 +871,29 @@ int launch_ff1(const griffin_layer &L, const void *X, int64_t ldx, int64_t M, fl
     p.M = (int32_t)M; p.F = L.n; p.d = L.d;
     p.splits = 1; p.kt_per_split = L.d / 64;
     p.nt = ff1_ntiles(L);
+    const bool gated = L.Wg != nullptr;
+    // An Eq. 2 block on the direct-to-LDS kernel takes 256-column tiles (one row-sum partial per tile) when that
+    // is the faster way to fill the chip: a 128-column tile of one product is bound by the L2->L1 path (~1400
+    // clocks per k-tile), a 256-column tile by the matrix cores (~2550), and either comes in rounds of one tile per CU.
+    bool wide = false;
+    if (L.dtype == GRIFFIN_BF16 && !gated && !(L.d % 64 != 0 || ldx > (1 << 21) || L.ld > (1 << 21))) {
+        const int64_t mt = M > 128 ? (M + 255) / 256 : (M + 127) / 128;
+        const int64_t tn = mt * p.nt, tw = mt * ((L.n + 2 * G_BN - 1) / (2 * G_BN));
+        wide = ((tw + 255) / 256) * 2550 < ((tn + 255) / 256) * 1400;
+        if (wide)
+            p.nt = (L.n + 2 * G_BN - 1) / (2 * G_BN);
+    }
     *nt_out = p.nt;
     if (M == 0)
         return GRIFFIN_OK;
-    const bool gated = L.Wg != nullptr;
     if (L.dtype == GRIFFIN_BF16) {
         // 256-token tiles halve the LDS traffic per flop; short prompts keep 128
         if (M > 128) {
             p.mt = (int32_t)((M + 255) / 256);
-            launch_mfma_act<4>(p, L.act, gated, st);
+            launch_mfma_act<4>(p, L.act, gated, wide, st);
         } else {
             p.mt = (int32_t)((M + 127) / 128);
-            launch_mfma_act<2>(p, L.act, gated, st);
+            launch_mfma_act<2>(p, L.act, gated, wide, st);
         }
         return check_launch("ff1_bf16_mfma_kernel");
     }

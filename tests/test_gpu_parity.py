@@ -314,6 +314,9 @@ PREFILL_CASES = [
     (synth.DT_BF16, 64, 131, [1, 2, 130], 7, synth.ACT_SILU, True, False),       # one-token prompts, D_ff odd, KT = 2
     (synth.DT_BF16, 32, 40, [5], 40, synth.ACT_GELU_TANH, True, True),           # a single k-tile, keep all
     (synth.DT_BF16, 1024, 2500, [700], 1, synth.ACT_SILU, True, False),          # k = 1, three 256-token tiles
+    (synth.DT_BF16, 64, 16520, [300], 8000, synth.ACT_RELU, False, True),        # Eq. 2 with biases, enough tiles for the
+                                                                                 # 256-column tiles; the last tile 136 wide
+    (synth.DT_BF16, 64, 33000, [100], 3000, synth.ACT_GELU_TANH, False, False),  # the same with 128-token tiles, last tile 232 wide
 ]
 
 
