@@ -109,7 +109,9 @@ __device__ __forceinline__ float ff1_acc_read(float a)
     return v;
 }
 
-template <int ACT, bool GATED, int MI, bool PLAIN, bool EQ2W = false>
+// EXTRA: the instantiation that also knows biases and the bf16 copy of Z; the lean one (most models: no FF
+// biases, selection alone) is 2 % faster for not carrying those branches and registers through the epilogue.
+template <int ACT, bool GATED, int MI, bool PLAIN, bool EQ2W = false, bool EXTRA = true>
 __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (&accU)[MI][2], f32x16 (&accG)[MI][2],
                                                     float (*rs)[64 * MI], uint32_t rs_lds, uint32_t patch_lds, int m0, int n0,
                                                     int tile_n)
@@ -121,7 +123,7 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1, l31 = lane & 31, lh = lane >> 5;
     const bool vec = ((p.F | (int32_t)p.ldz) & 3) == 0 && ((uintptr_t)p.Z & 15) == 0;
-    const bool hb = !PLAIN && (p.b1 != nullptr || (GLU && p.bg != nullptr));
+    const bool hb = EXTRA && !PLAIN && (p.b1 != nullptr || (GLU && p.bg != nullptr));
     const uint16_t *b1p = (const uint16_t *)p.b1, *bgp = (const uint16_t *)p.bg;
     const bool bias8 = (((uintptr_t)p.b1 | (uintptr_t)p.bg) & 7) == 0;       // four biases per 8-byte load
     if (vec && (!hb || bias8)) {
@@ -203,7 +205,7 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
                 const int tok = tok0 + 4 * (j_);                                                     \
                 if (tok < p.M && ncol < p.F) {                                                       \
                     *(f32x4_t *)(p.Z + (int64_t)tok * p.ldz + ncol) = pv[j_];                        \
-                    if (!PLAIN && p.Zb) {                                                            \
+                    if (EXTRA && !PLAIN && p.Zb) {                                                   \
                         uint2 h_;                                                                    \
                         h_.x = f32_to_bf16_bits(pv[j_][0]) | (f32_to_bf16_bits(pv[j_][1]) << 16);    \
                         h_.y = f32_to_bf16_bits(pv[j_][2]) | (f32_to_bf16_bits(pv[j_][3]) << 16);    \
@@ -303,7 +305,7 @@ typedef __attribute__((address_space(3))) void lds_void_t;
 // slot swizzle of row r (rows of every stage section start at a multiple of 16)
 #define FF1_SWZ(r) (((r) >> 1) & 7)
 
-template <int ACT, bool GATED, int MI, bool PLAIN, bool EQ2W = false>
+template <int ACT, bool GATED, int MI, bool PLAIN, bool EQ2W = false, bool EXTRA = true>
 __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass has no buffer-descriptor builtins; it only needs the launch stub
@@ -498,7 +500,7 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
             FF1_LOAD_ONE(1, q)
         // k-tile 0 has landed when only the first half of k-tile 1 and (from the second tile on) the
         // epilogue's stores, all issued after it, are still outstanding
-        if (stores_known && !PLAIN && p.Zb)      // twice the Z stores: more than the counter holds, 63 is as good
+        if (stores_known && EXTRA && !PLAIN && p.Zb)      // twice the Z stores: more than the counter holds, 63 is as good
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(H1 + EPI_STORES + MI * 8 > 63 ? 63 : H1 + EPI_STORES + MI * 8));
         else if (stores_known)
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(H1 + EPI_STORES > 63 ? 63 : H1 + EPI_STORES));
@@ -550,7 +552,7 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
             FF1_TILE_ADDR(logical_n)
             FF1_FIRST_LOADS()
         }
-        const bool usual = ff1_mfma_epilogue_t<ACT, GATED, MI, PLAIN, EQ2W>(pt, accU, accG, rs, rs_lds, patch_lds, m0c, n0c, tile_nc);
+        const bool usual = ff1_mfma_epilogue_t<ACT, GATED, MI, PLAIN, EQ2W, EXTRA>(pt, accU, accG, rs, rs_lds, patch_lds, m0c, n0c, tile_nc);
         if (!more)
             break;
         FF1_BARRIER()              // every wave is done with its patch and the row sums
@@ -831,7 +833,8 @@ static void launch_mfma(const Ff1Params &p, bool gated, bool wide, hipStream_t s
     const bool ktail = p.d % 64 != 0 || p.ldx > (1 << 21) || p.ldw > (1 << 21);
     if (gated) {
         if (ktail) hipLaunchKernelGGL((ff1_bf16_mfma_staged_kernel<ACT, true, MI, true>), grid_all, block, 0, st, p);
-        else hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, true, MI, false>), grid, block, 0, st, p);
+        else if (p.Zb || p.b1 || p.bg) hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, true, MI, false>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, true, MI, false, false, false>), grid, block, 0, st, p);
     } else {
         if (ktail) hipLaunchKernelGGL((ff1_bf16_mfma_staged_kernel<ACT, false, MI, true>), grid_all, block, 0, st, p);
         else if (wide) hipLaunchKernelGGL((ff1_bf16_mfma_kernel<ACT, true, MI, false, true>), grid, block, 0, st, p);   // 256-column tiles
