@@ -349,6 +349,26 @@ def test_prefill_select_matches_oracle(dtype, d, F, lens, k, act, gated, bias):
             np.testing.assert_array_equal(idx[b], np.arange(k))
 
 
+def test_prefill_with_biases_at_odd_addresses():
+    """Biases need no alignment beyond their element size: vectors that start 2 bytes past an 8-byte boundary
+    take the element-wise store path of the first product and give the same sets and statistic."""
+    dtype, d, F, S, k, act = synth.DT_BF16, 256, 512, 200, 200, synth.ACT_SILU
+    c = synth.small_case(91, d, F, S, dtype, with_bias=True)
+    W1 = c["W1"].copy()
+    _, (s_ref,) = open_margin([c["X"]], c["Wg"], W1, act, dtype, [k], c["bg"], c["b1"])
+    L, t = dev_layer(c["Wg"], W1, c["W2"], act, dtype, c["bg"], c["b1"], c["b2"])
+    idx_a, s_a, Z_a = run_prefill(L, to_dev(c["X"], dtype), [0, S], k)
+    # the same biases one element into a larger buffer
+    shift = lambda v: torch.cat([torch.zeros(1, dtype=v.dtype, device="cuda"), v])[1:]
+    bg2, b12 = shift(t["bg"]), shift(t["b1"])
+    assert bg2.data_ptr() % 8 == 2 and b12.data_ptr() % 8 == 2
+    L2 = G.layer(t["W1"], t["W2"], t["Wg"], act=act, bg=bg2, b1=b12, b2=t["b2"])
+    idx_b, s_b, Z_b = run_prefill(L2, to_dev(c["X"], dtype), [0, S], k)
+    np.testing.assert_array_equal(idx_a[0], oracle.topk(s_ref, k))
+    np.testing.assert_array_equal(idx_b[0], idx_a[0])
+    assert max_rel(s_b[0], s_ref) <= TOL_S and max_rel(Z_b, Z_a) <= 1e-6
+
+
 def test_prefill_without_z_out_and_zero_row():
     dtype, d, F, S, k = synth.DT_F32, 64, 96, 20, 30
     c = synth.small_case(77, d, F, S, dtype)
