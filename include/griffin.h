@@ -64,11 +64,14 @@ typedef struct {
     const void *b2;   /* [d] or NULL */
     const void *W2t;  /* optional second copy of W2, output-feature-major: [d][ldt], row c holding
                          W2[0..n-1][c] (this IS the paper's W_2, D x n) followed by zeros up to
-                         ldt.  When a block has it, griffin_ff_decode and griffin_ff_decode_multi
-                         stream it instead of W2 for single rows, which lets every workgroup finish
-                         its own output features (no partial rows); such a block may leave W2 NULL
-                         if nothing else reads it.  griffin_compact fills it when the target
-                         block has it.  bf16 blocks with d a multiple of 512 only. */
+                         ldt.  When a block has it, griffin_ff_decode streams it instead of W2 for
+                         a single row (batch == 1), which lets every workgroup finish its own output
+                         features (no partial rows); such a block may leave W2 NULL if it is only
+                         ever used that way.  Every other route (batch > 1, griffin_ff_decode_multi,
+                         the indexed calls, griffin_compact's source) reads the neuron-major W2 and
+                         returns GRIFFIN_EUNSUPPORTED (GRIFFIN_EINVAL for griffin_compact) when it
+                         is NULL.  griffin_compact fills W2t when the target block has it.  bf16
+                         blocks with d a multiple of 512 only. */
     int64_t ldt;      /* row stride of W2t in elements: a multiple of 512, >= n; 0 without W2t */
 } griffin_layer;
 

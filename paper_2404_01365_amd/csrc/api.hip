@@ -418,6 +418,8 @@ int griffin_ff_decode_multi(const griffin_layer *Cs, int32_t batch, const void *
         if (rc != GRIFFIN_OK)
             return rc;
         const griffin_layer &a = Cs[0], &c = Cs[b];
+        if (!c.W2)          // per-row blocks are streamed neuron-major; a block that carries W2t alone has no kernel here
+            return GRIFFIN_EUNSUPPORTED;
         if (c.d != a.d || c.n != a.n || c.dtype != a.dtype || c.act != a.act || c.ld != a.ld ||
             (c.Wg == nullptr) != (a.Wg == nullptr) || (c.bg == nullptr) != (a.bg == nullptr) ||
             (c.b1 == nullptr) != (a.b1 == nullptr) || (c.b2 == nullptr) != (a.b2 == nullptr))

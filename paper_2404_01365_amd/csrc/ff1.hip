@@ -473,10 +473,14 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
         }                                                                                      \
     }
 
-    // k-tile 0 of a tile goes to stage 0 in full; of k-tile 1 the first half of the loads goes out with
-    // it when that leaves the other half of stage 1 (32 KB, the gate/up weights' part) free for the
-    // epilogue's patches of the tile before, i.e. for gated blocks; otherwise it follows the epilogue.
-    constexpr int EARLY1 = GATED ? H1 : 0;
+    // k-tile 0 of a tile goes to stage 0 in full.  Of k-tile 1 only loads that fill the X section of
+    // stage 1 may go out with it: the weights' part of stage 1 (32 KB from its W1 section on) holds the
+    // epilogue's patches of the tile before, so a load into it has to follow the epilogue.  With 256-token
+    // tiles the first half of the loads is exactly the X regions; with 128-token tiles it would reach two
+    // W1 regions, which therefore wait.  Blocks with one weight section keep the patches at the head of
+    // stage 1 and send nothing early.
+    constexpr int EARLY1 = GATED ? (H1 < XQ ? H1 : XQ) : 0;
+    static_assert(EARLY1 <= XQ, "early loads of k-tile 1 must stay inside the X section of stage 1");
     // Global store instructions that EVERY wave issues in the epilogue's usual path on a tile that lies
     // wholly inside the matrix (8 per 32-token block, plus the row sums when all four waves write them).
     // The wait for k-tile 0 of the next tile may leave that many operations outstanding, no more: a

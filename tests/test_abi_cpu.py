@@ -121,6 +121,16 @@ def test_compact_and_decode_reject_bad_arguments_without_hip():
     two = (G.griffin_layer * 2)(mk(n=344), mk(n=300))
     assert lib.griffin_ff_decode_multi(two, 2, FAKE, FAKE, FAKE, 1 << 30, None) == G.ESHAPE
     assert lib.griffin_ff_decode_multi(None, 2, FAKE, FAKE, FAKE, 1 << 30, None) == G.EINVAL
+    # per-row blocks are streamed neuron-major: a block that carries only the transposed copy of W2 is
+    # refused on the host (no launch), whichever row it belongs to
+    def only_w2t():
+        B = mk(d=512, n=512, dtype=G.BF16, W2=None)
+        B.W2t, B.ldt = FAKE, 512
+        return B
+    assert lib.griffin_ff_decode_multi((G.griffin_layer * 2)(only_w2t(), only_w2t()), 2, FAKE, FAKE, FAKE, 1 << 30, None) == G.EUNSUPPORTED
+    assert lib.griffin_ff_decode_multi((G.griffin_layer * 2)(mk(d=512, n=512, dtype=G.BF16), only_w2t()), 2,
+                                       FAKE, FAKE, FAKE, 1 << 30, None) == G.EUNSUPPORTED
+    assert lib.griffin_ff_decode_multi((G.griffin_layer * 1)(only_w2t()), 1, FAKE, FAKE, FAKE, 1 << 30, None) == G.EUNSUPPORTED
 
     assert lib.griffin_topk(None, 1, 10, 3, FAKE, None) == G.EINVAL
     assert lib.griffin_topk(FAKE, 1, 10, 11, FAKE, None) == G.ESHAPE

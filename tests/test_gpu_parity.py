@@ -349,6 +349,71 @@ def test_prefill_select_matches_oracle(dtype, d, F, lens, k, act, gated, bias):
             np.testing.assert_array_equal(idx[b], np.arange(k))
 
 
+# ------------------------------------------------------------------ prefill: workgroups that walk several tiles
+# The matrix-core kernel runs one workgroup per CU; with more tiles than CUs (every full-size config) each
+# workgroup walks through several tiles, sends the next tile's first loads before the epilogue of the
+# current one and decides from the kind of tile it just finished (whole, or ragged in tokens or neurons)
+# how many stores may still be outstanding when it starts to read.  These cases have 280 to 780 tiles at a
+# small model width, so that the oracle stays cheap, two or three k-tiles, ragged last tiles in both
+# directions, and a token-tile count coprime to the walking stride so that whole and ragged tiles alternate
+# within one workgroup.
+WALK_CASES = [
+    # dtype, d, F, lens, k, act, gated, bias
+    (synth.DT_BF16, 192, 11000, [1700], 5500, synth.ACT_SILU, True, False),        # 7 x 86 = 602 tiles, lean kernel
+    (synth.DT_BF16, 128, 11000, [900, 800], 4000, synth.ACT_GELU_TANH, True, True),  # the same walk with biases, two prompts
+    (synth.DT_BF16, 128, 16600, [1000], 8000, synth.ACT_RELU, False, True),        # Eq. 2, 128-column tiles: 4 x 130 = 520
+    (synth.DT_BF16, 128, 16520, [1300], 8000, synth.ACT_GELU_TANH, False, True),   # Eq. 2, 256-column tiles: 6 x 65 = 390
+    (synth.DT_BF16, 128, 33000, [100], 9000, synth.ACT_SILU, True, False),         # 128-token tiles: 258 of them, lean
+    (synth.DT_BF16, 64, 40000, [128], 20000, synth.ACT_SILU, True, True),          # 128-token tiles with biases: 313
+    (synth.DT_BF16, 64, 66000, [90], 30000, synth.ACT_RELU, False, False),         # Eq. 2, 128-token tiles, 516 narrow tiles
+    (synth.DT_BF16, 64, 128000, [70], 50000, synth.ACT_SILU, False, True),         # Eq. 2, 128-token tiles, 500 wide tiles
+]
+
+
+@pytest.mark.parametrize("dtype,d,F,lens,k,act,gated,bias", WALK_CASES)
+def test_prefill_select_when_workgroups_walk_tiles(dtype, d, F, lens, k, act, gated, bias):
+    test_prefill_select_matches_oracle(dtype, d, F, lens, k, act, gated, bias)
+
+
+@pytest.mark.parametrize("d,F,lens,k,gated,bias", [
+    (192, 11000, [1700], 5000, True, False),     # the first product leaves the bf16 copy of Z while it walks 602 tiles
+    (128, 11000, [1000, 700], 5000, True, True), # the same with biases
+    (64, 40000, [100], 20000, True, False),      # 128-token tiles, 313 of them
+])
+def test_prompt_phase_when_workgroups_walk_tiles(d, F, lens, k, gated, bias):
+    test_prompt_phase_is_selection_plus_prompt_output_from_one_z(synth.DT_BF16, d, F, lens, k, gated, bias)
+
+
+@pytest.mark.parametrize("d,F,S,bias", [
+    (4200, 320, 6000, True),      # 24 x 17 = 408 output tiles of 256 x 256, five k-tiles, ragged in both directions
+    (66000, 128, 100, False),     # a 128-token tile and 258 feature tiles
+    (5000, 8192, 3300, True),     # the contraction cut into ranges AND more work items than CUs
+])
+def test_prompt_output_when_workgroups_walk_tiles(d, F, S, bias):
+    """The second product of the prompt phase (Section 5.1) on the same kernel in its plain mode."""
+    dtype = synth.DT_BF16
+    g = np.random.default_rng(d + F + S)
+    Z = (g.standard_normal((S, F)) * (g.random((S, F)) < 0.7)).astype(np.float32)
+    W2 = synth.round_to_bf16((g.standard_normal((F, d)) * F ** -0.5).astype(np.float32))     # neuron-major
+    b2 = synth.round_to_bf16((g.standard_normal(d) * 0.1).astype(np.float32)) if bias else None
+    W2p = to_dev(np.ascontiguousarray(W2.T), dtype)
+    Y = torch.full((S, d), float("nan"), dtype=W2p.dtype, device="cuda")
+    G.griffin_ff_prompt_out(torch.from_numpy(Z).cuda(), W2p, Y, b2=to_dev(b2, dtype),
+                            workspace=workspace(G.griffin_prompt_out_workspace_bytes(S, F, d)))
+    sync()
+    got = to_host(Y)
+    assert np.all(np.isfinite(got))
+    # rows of Y are independent (Eq. 1 row-wise): where the oracle's plain loops would take minutes for all
+    # of them, every 11th token goes through it (some of every token tile, at all lane positions), whole rows
+    rows = np.arange(S) if S * F * d < 2e10 else np.arange(0, S, 11)
+    # the device rounds Z to bf16 on its way into the matrix cores: the reference does the same rounding
+    # and nothing else (fp64 sums), so what is left is the rounding of Y itself
+    Y_ref = oracle.ff2(synth.round_to_bf16(Z[rows]).astype(np.float64), W2, b2)
+    assert max_rel(got[rows], Y_ref) <= 2.0 ** -8
+    if rows.size == S:          # and against the unrounded Z, at the tolerance of the outputs
+        assert max_rel(got, oracle.ff2(Z.astype(np.float64), W2, b2)) <= TOL_OUT[dtype]
+
+
 def test_prefill_with_biases_at_odd_addresses():
     """Biases need no alignment beyond their element size: vectors that start 2 bytes past an 8-byte boundary
     take the element-wise store path of the first product and give the same sets and statistic."""
