@@ -185,6 +185,24 @@ int griffin_ff_decode(const griffin_layer *C, const void *x, void *y, int32_t ba
                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * griffin_ff_decode for callers that cannot allocate device memory or carry a workspace around:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and bit for bit the same y as griffin_ff_decode, but the partial rows live
+ * in a device array inside the library (8 MiB per GPU, held from the first call on that GPU until the
+ * process ends) instead of a caller workspace.  The call allocates and frees nothing.
+ *   - A request whose griffin_decode_workspace_bytes(C->d, C->n, batch) exceeds
+ *     griffin_ff_decode_static_max_bytes() (8 MiB: one row at any width the library decodes, i.e.
+ *     d <= 8192; two rows up to d = 4096) returns GRIFFIN_EWORKSPACE and enqueues nothing.
+ *   - The current device must be the one `stream` belongs to (as for every entry point); the first
+ *     call on a device looks the array's address up (GRIFFIN_EHIP if the runtime refuses).
+ *   - All calls on one GPU share the array: calls on different streams of one GPU that may overlap
+ *     race on it.  Calls on one stream are ordered and need nothing between them; the array needs
+ *     no clearing (every word that is read was written by the same call).
+ */
+size_t griffin_ff_decode_static_max_bytes(void);
+int griffin_ff_decode_static(const griffin_layer *C, const void *x, void *y, int32_t batch, void *stream);
+
+/*
  * Per-sequence expert sets (every sample picks its own neurons, Section 4.2): row b of x goes
  * through its own compact block Cs[b].  Cs is a HOST array of `batch` HOST structs that must
  * agree in d, n, dtype, act, ld and in which optional pointers are NULL.

@@ -78,6 +78,8 @@ _SIGS = {
     "griffin_prompt_phase_workspace_bytes": (_sz, [_LP, _i64, _i32]),
     "griffin_prompt_phase": (ctypes.c_int, [_LP, _vp, _i64, _vp, _i64, _IP, _i32, _i32, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
     "griffin_ff_decode": (ctypes.c_int, [_LP, _vp, _vp, _i32, _vp, _sz, _vp]),
+    "griffin_ff_decode_static_max_bytes": (_sz, []),
+    "griffin_ff_decode_static": (ctypes.c_int, [_LP, _vp, _vp, _i32, _vp]),
     "griffin_ff_decode_multi": (ctypes.c_int, [_LP, _i32, _vp, _vp, _vp, _sz, _vp]),
     "griffin_ff_decode_indexed": (ctypes.c_int, [_LP, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
     "griffin_index_sets_bytes": (_sz, [_i32, _i32]),
@@ -221,6 +223,16 @@ def griffin_decode_workspace_bytes(d: int, n: int, batch: int = 1) -> int:
 def griffin_ff_decode(C: griffin_layer, x, y, batch: int = 1, *, workspace, stream=None) -> None:
     _check(lib.griffin_ff_decode(ctypes.byref(C), _ptr(x), _ptr(y), batch, _ptr(workspace),
                                  _nbytes(workspace), _stream(stream)), "griffin_ff_decode")
+
+
+def griffin_ff_decode_static_max_bytes() -> int:
+    return int(lib.griffin_ff_decode_static_max_bytes())
+
+
+def griffin_ff_decode_static(C: griffin_layer, x, y, batch: int = 1, *, stream=None) -> None:
+    """griffin_ff_decode with the partial rows in the library's own device array (no workspace)."""
+    _check(lib.griffin_ff_decode_static(ctypes.byref(C), _ptr(x), _ptr(y), batch, _stream(stream)),
+           "griffin_ff_decode_static")
 
 
 def griffin_ff_decode_multi(Cs: Sequence[griffin_layer], x, y, *, workspace, stream=None) -> None:

@@ -3,6 +3,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "common.h"
 
 namespace griffin {
@@ -439,6 +441,60 @@ int griffin_ff_decode_indexed(const griffin_layer *L, const int32_t *idx, int32_
     if (k < 1 || k > L->n)
         return GRIFFIN_ESHAPE;
     return decode_common(L, nullptr, idx, k, batch, x, y, workspace, workspace_bytes, stream);
+}
+
+// ---------------------------------------------------------------- decode without a caller workspace
+// The partial rows of griffin_ff_decode live in a file-scope device array instead of a workspace the
+// caller allocated.  In host code the array's name is only a handle: its device address is asked for
+// once per device (with that device current) and that address is what the kernels are given.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)8 << 20;
+constexpr int STATIC_MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+static std::atomic<void *> g_scratch_ptr[STATIC_MAX_DEVICES];
+
+// device address of this device's copy of the array; GRIFFIN_EHIP if the runtime cannot give it
+static int static_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return set_hip_error(e, "hipGetDevice");
+    if (dev < 0 || dev >= STATIC_MAX_DEVICES)
+        return GRIFFIN_EUNSUPPORTED;
+    void *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        // two threads may both ask; they get the same address
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return set_hip_error(e, "hipGetSymbolAddress(scratch)");
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return GRIFFIN_OK;
+}
+
+size_t griffin_ff_decode_static_max_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+int griffin_ff_decode_static(const griffin_layer *C, const void *x, void *y, int32_t batch, void *stream)
+{
+    int rc = check_layer(C);
+    if (rc != GRIFFIN_OK)
+        return rc;
+    if (batch < 0 || !x || !y)
+        return GRIFFIN_EINVAL;
+    if (batch > GRIFFIN_MAX_BATCH)
+        return GRIFFIN_EUNSUPPORTED;
+    // sizes are judged before the runtime is touched: what griffin_ff_decode would ask of a workspace
+    // must fit the array
+    const size_t need = griffin_decode_workspace_bytes(C->d, C->n, batch ? batch : 1);
+    if (need == 0 || need > STATIC_SCRATCH_BYTES)
+        return GRIFFIN_EWORKSPACE;
+    if (batch == 0)
+        return GRIFFIN_OK;
+    void *ptr = nullptr;
+    if ((rc = static_scratch(&ptr)) != GRIFFIN_OK)
+        return rc;
+    return decode_common(C, nullptr, nullptr, 0, batch, x, y, ptr, need, stream);
 }
 
 size_t griffin_index_sets_bytes(int32_t n, int32_t batch)

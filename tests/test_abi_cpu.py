@@ -224,3 +224,17 @@ def test_batch_decode_workspace_covers_the_matrix_core_path():
     assert G.griffin_decode_workspace_bytes(d, n, 16) <= G.griffin_decode_workspace_bytes(d, n, 64)
     # shapes the matrix-core path does not take keep the four-rows-per-pass size
     assert G.griffin_decode_workspace_bytes(8192, 500, 16) == G.griffin_decode_workspace_bytes(8192, 500, 13) // 13 * 16
+
+
+def test_decode_static_judges_sizes_before_it_touches_the_runtime():
+    lib = G.lib
+    assert G.griffin_ff_decode_static_max_bytes() == 8 << 20
+    C = mk(d=4096, n=5504, dtype=G.BF16)
+    # C, x, y, batch, stream
+    assert lib.griffin_ff_decode_static(None, FAKE, FAKE, 1, None) == G.EINVAL
+    assert lib.griffin_ff_decode_static(ctypes.byref(C), None, FAKE, 1, None) == G.EINVAL
+    assert lib.griffin_ff_decode_static(ctypes.byref(C), FAKE, FAKE, G.MAX_BATCH + 1, None) == G.EUNSUPPORTED
+    assert G.griffin_decode_workspace_bytes(4096, 5504, 1) <= G.griffin_ff_decode_static_max_bytes()
+    assert G.griffin_decode_workspace_bytes(4096, 5504, 16) > G.griffin_ff_decode_static_max_bytes()
+    assert lib.griffin_ff_decode_static(ctypes.byref(C), FAKE, FAKE, 16, None) == G.EWORKSPACE     # more than the array holds
+    assert lib.griffin_ff_decode_static(ctypes.byref(C), FAKE, FAKE, 0, None) == G.OK              # nothing to do
