@@ -7,9 +7,10 @@ selected neurons, and T generated tokens through the pruned FF block, for every 
 workload.  Inputs are resident in HBM before the timed region.  Decode cycles through enough
 copies of the compact weights (>= 1 GiB) that the 256 MB Infinity Cache cannot serve them.
 
-Prints ONE JSON line: whole-job decode tokens/s (`value`), the roofline of the dominant
+Prints ONE JSON line: whole-job generated tokens/s (`value`), the roofline of the dominant
 kernel (the weight-streaming decode kernel, HBM-bound) and the CPU oracle timed on a bounded
-sample of the same workload.
+sample of the same workload.  The default workload is config 3 (the Llama-2-13B-shaped stack of 40
+layers, the model of the paper's latency table); configs 1 and 2 ride along as short extra runs.
 """
 from __future__ import annotations
 
@@ -31,8 +32,11 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=1, help="workload: 1 Llama-2-7B-shaped layer, 2 Gemma-7B-shaped layer, 3 Llama-2-13B-shaped stack of 40, "
+    ap.add_argument("--config", type=int, default=3, help="workload: 3 Llama-2-13B-shaped stack of 40 layers (default: the largest single-sequence "
+                         "workload, the model of the paper's latency table), 1 Llama-2-7B-shaped layer, 2 Gemma-7B-shaped layer, "
                          "4 Mistral-7B-shaped stack of 8 with 16 sequences that keep their own sets")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short runs of configs 1 and 2 that the default run reports as extra keys")
     ap.add_argument("--k", type=int, default=0, help="kept neurons (default: the config's 50%% point)")
     ap.add_argument("--layers", type=int, default=0, help="layers to run (default: all of the config)")
     ap.add_argument("--probe-every", type=int, default=8, help="decode steps between kernel-duration probes")
@@ -79,13 +83,18 @@ class Hip:
 
 
 def cpu_baseline(cfg, k, Wg, W1, W2, seconds_target=12.0):
-    """The oracle as it stands, timed on this host: decode tokens through a compact block."""
+    """The oracle as it stands, timed on this host's cores on a bounded sample of the workload: the prompt
+    phase (FF activations, statistic, top-k) of ONE layer and ONE prompt, and decode tokens through that
+    layer's compact block."""
     import numpy as np
     import oracle
     import synth
-    S_sel = 32
-    X = synth.prompt(cfg, 0)[:S_sel]
+    lens = synth.seq_lengths(cfg)
+    b_sel = int(np.argmin(lens))                      # the shortest prompt of a batched workload; the only one otherwise
+    X = synth.prompt(cfg, 0, b_sel, lens[b_sel])
+    t0 = time.perf_counter()
     idx, _ = oracle.prefill_select(X, Wg, W1, cfg.act, k)
+    sel_s = time.perf_counter() - t0
     cw = [oracle.compact(w, idx) for w in (Wg, W1, W2)]
     xt = synth.decode_inputs(cfg, 0, steps=8).astype(np.float64)
     oracle.ff_decode(xt[0], *cw, cfg.act)
@@ -96,10 +105,14 @@ def cpu_baseline(cfg, k, Wg, W1, W2, seconds_target=12.0):
         el = time.perf_counter() - t0
         if el >= seconds_target or n >= 512:
             break
+    per_layer_token_s = el / n
     return {
-        "value": n / el, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-        "sample": "%d decode tokens through one layer's k=%d compact block in fp64 (selection for the "
-                  "sample taken by the oracle on the first %d prompt rows, untimed)" % (n, k, S_sel),
+        "value": 1.0 / (per_layer_token_s * cfg.n_layers), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": "%d decode tokens through ONE layer's k=%d compact block in fp64 (%.1f ms per layer-token; value = 1 / (that x %d layers)); "
+                  "prompt phase of one layer on one prompt of %d tokens: %.2f s"
+                  % (n, k, per_layer_token_s * 1e3, cfg.n_layers, lens[b_sel], sel_s),
+        "decode_ms_per_layer_token": per_layer_token_s * 1e3,
+        "select_s_per_layer": sel_s, "select_sample_tokens": lens[b_sel],
     }
 
 
@@ -265,6 +278,33 @@ def main():
             print("bench.py: config %d is a parity case, not a bench line" % args.config, file=sys.stderr)
             sys.exit(2)
         return run_batched(args, cfg, torch, np, G, synth, hip)
+    if cfg.dtype != synth.DT_BF16:
+        print("bench.py: config %d is a parity case, not a bench line" % args.config, file=sys.stderr)
+        sys.exit(2)
+    out = run_single(args, cfg, torch, np, G, synth, hip, brief=False)
+    if args.config == 3 and not args.no_other_configs and not args.k and not args.layers:
+        # the two single-layer workloads, a few steps each, as extra keys beside the headline line
+        import copy
+        for cid in (1, 2):
+            a = copy.copy(args)
+            a.steps, a.warmup, a.config = 3, 1, cid
+            torch.cuda.empty_cache()
+            o = run_single(a, synth.CONFIGS[cid], torch, np, G, synth, hip, brief=True)
+            out["config%d" % cid] = {
+                "workload": o["config"]["workload"], "tokens_per_s": o["value"], "ms_per_step": o["ms_per_step"],
+                "roofline_frac": o["roofline"]["frac"], "avg_kernel_us": o["roofline"]["avg_kernel_us"],
+                "us_per_layer_token": o["decode"]["us_per_layer_token"],
+                "frac_per_layer_token": o["decode"]["GBps_per_layer_token"] / HBM_PEAK_GBS,
+                "pruned_over_full_latency": o["decode"]["pruned_over_full_latency"],
+                "select_us_per_layer": o["select_us_per_layer"], "select": o["select"],
+            }
+    print(json.dumps(out))
+
+
+def run_single(args, cfg, torch, np, G, synth, hip, brief):
+    """One sequence, n_layers independent FF blocks: one step = selection + compaction of every layer, then T
+    tokens through every layer's compact block.  `brief` leaves out what is measured beside the timed region
+    except the full-width comparison."""
     k = args.k or cfg.k
     n_layers = args.layers or cfg.n_layers
     T, d, F, S = cfg.decode_steps, cfg.d, cfg.d_ff, cfg.prompt_len
@@ -277,15 +317,17 @@ def main():
         return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
 
     # ---------------- inputs resident in HBM
+    from concurrent.futures import ThreadPoolExecutor
     layers, host_w0 = [], None
-    for l in range(n_layers):
-        Wg, W1, W2 = synth.layer_weights(cfg, l)
-        if l == 0:
-            host_w0 = (Wg, W1, W2)
-        t = dict(Wg=up(Wg), W1=up(W1), W2=up(W2), X=up(synth.prompt(cfg, l)), xt=up(synth.decode_inputs(cfg, l)))
-        t["L"] = G.layer(t["W1"], t["W2"], t["Wg"], act=cfg.act)
-        layers.append(t)
-        del Wg, W1, W2
+    with ThreadPoolExecutor(synth.n_threads()) as pool:
+        for l in range(n_layers):
+            Wg, W1, W2 = synth.layer_weights(cfg, l, pool=pool)
+            if l == 0:
+                host_w0 = (Wg, W1, W2)
+            t = dict(Wg=up(Wg), W1=up(W1), W2=up(W2), X=up(synth.prompt(cfg, l)), xt=up(synth.decode_inputs(cfg, l)))
+            t["L"] = G.layer(t["W1"], t["W2"], t["Wg"], act=cfg.act)
+            layers.append(t)
+            del Wg, W1, W2
 
     compact_bytes = 3 * k * d * w
     if args.warm or n_layers * compact_bytes >= (1 << 30):
@@ -396,9 +438,28 @@ def main():
         for t in layers:
             t["Lf"], t["Lft"] = [], []
 
+    # selection (FF activations, statistic, top-k) and compaction timed apart, outside the timed region
+    se = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    reps_s = max(1, 8 // n_layers)
+    for rep in range(2):
+        if rep == 1:
+            se[0].record()
+        for r in range(reps_s):
+            for t in layers:
+                G.griffin_prefill_select(t["L"], t["X"], cu, k, t["idx"], workspace=ws_pre, stream=stream)
+    se[1].record()
+    for r in range(reps_s):
+        for t in layers:
+            G.griffin_compact(t["L"], t["idx"], k, t["C"][0], stream=stream)
+    se[2].record()
+    torch.cuda.synchronize()
+    presel_us = se[0].elapsed_time(se[1]) * 1e3 / (reps_s * n_layers)
+    comp_us = se[1].elapsed_time(se[2]) * 1e3 / (reps_s * n_layers)
+    comp_bytes = 2 * 3 * k * d * w
+
     # the prompt's own full-width output Y = Z W_2^T (Section 5.1), outside the timed region
     prompt_out_us = prompt_phase_us = None
-    if not args.skip_full_width:
+    if not args.skip_full_width and not brief:
         t0l = layers[0]
         Zbuf = torch.empty((S, F), dtype=torch.float32, device="cuda")
         G.griffin_prefill_select(t0l["L"], t0l["X"], cu, k, t0l["idx"], Z_out=Zbuf, workspace=ws_pre, stream=stream)
@@ -429,7 +490,7 @@ def main():
     # further rows measured outside the timed region: the static weight-norm selector (Section 5.1
     # setup) and one shared set decoded for a batch of 16 rows (Section 5.3, Eq. 7)
     extras = None
-    if not args.skip_full_width:
+    if not args.skip_full_width and not brief:
         t0l = layers[0]
         sc = torch.empty((F,), dtype=torch.float32, device="cuda")
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
@@ -538,6 +599,8 @@ def main():
             "bound": "hbm", "kernel": kern_name,
             "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": traffic,
+            "traffic_source": None if traffic is None else "profiles/traffic.json: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this command, "
+                              "scaled by the same counters on a copy kernel of known size (stored, not re-measured in this run)",
             "algorithmic_bytes_per_launch": kern_bytes,
             "avg_kernel_us": avg_us, "median_kernel_us": kern_us[len(kern_us) // 2], "launches_timed": len(kern_us),
             "raw_event_span_us": sum(raw_us) / len(raw_us), "event_cost_us": event_overhead_us,
@@ -554,6 +617,11 @@ def main():
             "pruned_over_full_latency": (u / full_us) if full_us else None,
         },
         "select_us_per_layer": sel_ms * 1e3 / n_layers,
+        "select": {
+            "prefill_select_us_per_layer": presel_us, "prefill_select_TFLOPs_whole_call": 4.0 * S * F * d / (presel_us * 1e-6) / 1e12,
+            "compact_us_per_layer": comp_us, "compact_GBps": comp_bytes / (comp_us * 1e-6) / 1e9,
+            "compact_frac_of_peak": comp_bytes / (comp_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+        },
         "prompt_out": None if prompt_out_us is None else {
             "us_per_layer": prompt_out_us, "TFLOPs": 2.0 * S * F * d / (prompt_out_us * 1e-6) / 1e12},
         "prompt_phase_one_call": None if prompt_phase_us is None else {
@@ -561,9 +629,9 @@ def main():
     }
     if extras:
         out.update(extras)
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not brief:
         out["cpu_baseline"] = cpu_baseline(cfg, k, *host_w0)
-    print(json.dumps(out))
+    return out
 
 
 if __name__ == "__main__":

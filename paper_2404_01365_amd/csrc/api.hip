@@ -76,14 +76,13 @@ static int fill_seq_table(const int32_t *cu, int32_t n_seqs, SeqTable &t, int64_
 
 struct PrefillPlan {
     size_t off_z, off_rowpart, off_w, off_s2part, off_s, total;
-    int nt, rc;
+    int nt;
 };
 
 static PrefillPlan plan_prefill(const griffin_layer &L, int64_t total_tokens, int32_t n_seqs, bool have_z)
 {
     PrefillPlan pl;
     pl.nt = ff1_ntiles(L);
-    pl.rc = stat_row_chunks(total_tokens, n_seqs, L.n);
     size_t off = 0;
     pl.off_z = off;
     if (!have_z)
@@ -93,7 +92,7 @@ static PrefillPlan plan_prefill(const griffin_layer &L, int64_t total_tokens, in
     pl.off_w = off;
     off += align256((size_t)total_tokens * sizeof(float));
     pl.off_s2part = off;
-    off += align256((size_t)n_seqs * pl.rc * L.n * sizeof(float));
+    off += align256((size_t)stat_max_chunks(total_tokens, n_seqs, L.n) * L.n * sizeof(float));
     pl.off_s = off;
     off += align256((size_t)n_seqs * L.n * sizeof(float));
     pl.total = off;
@@ -178,7 +177,7 @@ int griffin_prefill_select(const griffin_layer *L, const void *X, int64_t ldx,
     int32_t nt = 0;
     if ((rc = launch_ff1(*L, X, ldx, total, Z, zld, rowpart, &nt, st)) != GRIFFIN_OK)
         return rc;
-    if ((rc = launch_stat(Z, zld, rowpart, nt, total, L->n, seqs, pl.rc, w, s2part, s, s_out, st)) != GRIFFIN_OK)
+    if ((rc = launch_stat(Z, zld, rowpart, nt, total, L->n, seqs, w, s2part, s, s_out, st)) != GRIFFIN_OK)
         return rc;
     return launch_topk(s, n_seqs, L->n, k, idx_out, st);
 }
@@ -343,7 +342,7 @@ int griffin_prompt_phase(const griffin_layer *L, const void *W2p, int64_t ldw, c
     int32_t nt = 0;
     if ((rc = launch_ff1(*L, X, ldx, total, Z, L->n, rowpart, &nt, st, fuse ? (uint16_t *)ws2 : nullptr, L->n)) != GRIFFIN_OK)
         return rc;
-    if ((rc = launch_stat(Z, L->n, rowpart, nt, total, L->n, seqs, pl.rc, w, s2part, s, s_out, st)) != GRIFFIN_OK)
+    if ((rc = launch_stat(Z, L->n, rowpart, nt, total, L->n, seqs, w, s2part, s, s_out, st)) != GRIFFIN_OK)
         return rc;
     if ((rc = launch_topk(s, n_seqs, L->n, k, idx_out, st)) != GRIFFIN_OK)
         return rc;

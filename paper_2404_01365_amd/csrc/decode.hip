@@ -243,12 +243,20 @@ __device__ __forceinline__ void decode_body(const DecodeParams &p, const void *W
             }
             __syncthreads();
         }
+        // The partial row is private to this kernel and the one that adds the rows up, so its columns are
+        // stored in the order that makes every store instruction one contiguous kilobyte: quad e/4 of
+        // chunk c goes to float4 slot (e/4) * nch + c (a lane's 8 columns would otherwise leave as two
+        // instructions that each fill every other 16 bytes).
         if (team == 0 && valid && b + nb < p.batch) {
-            float *out = p.part + ((int64_t)(b + nb) * p.P + blockIdx.x) * d + c * E;
+            float *out = p.part + ((int64_t)(b + nb) * p.P + blockIdx.x) * d;
 #pragma unroll
             for (int e = 0; e < E; e += 4) {
                 const f32x4 v = {ya[nb][e], ya[nb][e + 1], ya[nb][e + 2], ya[nb][e + 3]};
-                __builtin_nontemporal_store(v, (f32x4 *)(out + e));
+#ifdef DEC_PLAIN_STORE
+                *(f32x4 *)(out + (int64_t)((e / 4) * nch + c) * 4) = v;
+#else
+                __builtin_nontemporal_store(v, (f32x4 *)(out + (int64_t)((e / 4) * nch + c) * 4));
+#endif
             }
         }
     }
@@ -275,38 +283,65 @@ struct B2Ptrs {
     const void *p[GRIFFIN_MAX_BATCH];    // b2 of every row's own block (multi path)
 };
 
-// y[b][c..c+3] = sum_p part[b][p][c..c+3] + b2, p taken in a fixed order.  One wavefront per
-// column quad: lane l adds rows l, l+64, ... and the wave finishes with DPP sums.
+// y[b] = sum_p part[b][p] + b2, the rows p taken in a fixed order.  A workgroup of eight wavefronts owns
+// RED_Q float4 slots (one 128-byte line) of every partial row: lane (r, q) of wave w reads slot q of the
+// rows p = 8 w + r, + 64, + 128, + 192 (all four loads on their way at once; a wave instruction covers
+// eight whole lines), adds them in that order, the eight lanes of a slot are added with wave shuffles and
+// the eight waves through LDS.  nch > 0 says that the rows come from the streaming kernel, which stores
+// quad h of 16-byte chunk c at slot h * nch + c (bf16 blocks: 8 columns per chunk); 0 = columns in order.
+constexpr int RED_Q = 8, RED_WAVES = 8;
 template <bool BF16, bool MULTI>
-__global__ __launch_bounds__(256) void ff_decode_reduce_kernel(const float *part, int P, int d,
-                                                               const void *b2_one, B2Ptrs b2_multi,
-                                                               void *y)
+__global__ __launch_bounds__(RED_WAVES * 64) void ff_decode_reduce_kernel(const float *part, int P, int d, int nch,
+                                                                           const void *b2_one, B2Ptrs b2_multi,
+                                                                           void *y)
 {
-    const int lane = threadIdx.x & 63;
+    __shared__ float4 fold[RED_WAVES][RED_Q];
+#ifdef DEC_RED_EMPTY
+    if (P > 0) return;
+#endif
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int b = blockIdx.y;
-    const int c = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 4;
-    if (c >= d)
-        return;
-    const void *b2 = MULTI ? b2_multi.p[b] : b2_one;
-    const float *base = part + (int64_t)b * P * d + c;
-    // four rows per lane on their way at once (256 partial rows: all of them); one load per trip of a
-    // loop would put that many memory latencies in a row.  Same order of additions as row by row.
+    const int r = lane >> 3, qi = lane & 7;
+    const int nq = d >> 2;
+    const int q = blockIdx.x * RED_Q + qi;
+    const int qc = q < nq ? q : nq - 1;            // clamped: loads stay in bounds, the result is not stored
+    const float *base = part + (int64_t)b * P * d + (int64_t)qc * 4;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int p0 = lane; p0 < P; p0 += 256) {
+    for (int p0 = wave * 8 + r; p0 < P; p0 += 256) {
         float4 t[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int pp = p0 + 64 * i;
-            t[i] = pp < P ? *(const float4 *)(base + (int64_t)pp * d) : make_float4(0.f, 0.f, 0.f, 0.f);
+#ifdef DEC_PLAIN_LOAD
+            const f32x4 v = pp < P ? *(const f32x4 *)(base + (int64_t)pp * d) : (f32x4){0.f, 0.f, 0.f, 0.f};
+#else
+            const f32x4 v = pp < P ? __builtin_nontemporal_load((const f32x4 *)(base + (int64_t)pp * d)) : (f32x4){0.f, 0.f, 0.f, 0.f};
+#endif
+            t[i] = make_float4(v.x, v.y, v.z, v.w);
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             acc.x += t[i].x; acc.y += t[i].y; acc.z += t[i].z; acc.w += t[i].w;
         }
     }
-    float4 s;
-    s.x = wave_sum(acc.x); s.y = wave_sum(acc.y); s.z = wave_sum(acc.z); s.w = wave_sum(acc.w);
-    if (lane == 0) {
+    // the eight lanes (r = 0..7) that hold the same slot
+#pragma unroll
+    for (int m = 8; m < 64; m <<= 1) {
+        acc.x += __shfl_xor(acc.x, m, 64); acc.y += __shfl_xor(acc.y, m, 64);
+        acc.z += __shfl_xor(acc.z, m, 64); acc.w += __shfl_xor(acc.w, m, 64);
+    }
+    if (r == 0)
+        fold[wave][qi] = acc;
+    __syncthreads();
+    if (threadIdx.x < RED_Q && q < nq) {
+        float4 s = fold[0][qi];
+#pragma unroll
+        for (int w = 1; w < RED_WAVES; ++w) {
+            const float4 v = fold[w][qi];
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+        const int c = nch > 0 ? (q % nch) * 8 + (q / nch) * 4 : q * 4;      // first of this slot's four columns
+        const void *b2 = MULTI ? b2_multi.p[b] : b2_one;
         if (b2) {
             s.x += load_scalar<BF16>(b2, c);
             s.y += load_scalar<BF16>(b2, c + 1);
@@ -324,6 +359,9 @@ __global__ __launch_bounds__(256) void ff_decode_reduce_kernel(const float *part
         }
     }
 }
+
+// grid of the kernel above for rows of d floats
+static dim3 reduce_grid(int d, int batch) { return dim3((d / 4 + RED_Q - 1) / RED_Q, batch); }
 
 // waves per team for a row of d elements, 0 if this build cannot cover it
 static int decode_team_waves(int32_t d, bool bf16)
@@ -421,8 +459,8 @@ int launch_decode(const DecodeJob &job, hipStream_t st)
             return rc;
         if (ev_mid && hipEventRecord(ev_mid, st) != hipSuccess)
             return set_hip_error(hipGetLastError(), "hipEventRecord");
-        dim3 rgrid((job.d / 4 + 3) / 4, job.batch), rblock(256);
-        hipLaunchKernelGGL((ff_decode_reduce_kernel<true, false>), rgrid, rblock, 0, st, job.part, P, job.d, b2, b2m, job.y);
+        dim3 rgrid = reduce_grid(job.d, job.batch), rblock(RED_WAVES * 64);
+        hipLaunchKernelGGL((ff_decode_reduce_kernel<true, false>), rgrid, rblock, 0, st, job.part, P, job.d, 0, b2, b2m, job.y);
         rc = check_launch("ff_decode_reduce_kernel");
         if (rc == GRIFFIN_OK && ev_end && hipEventRecord(ev_end, st) != hipSuccess)
             return set_hip_error(hipGetLastError(), "hipEventRecord");
@@ -467,17 +505,18 @@ int launch_decode(const DecodeJob &job, hipStream_t st)
     if (ev_mid && hipEventRecord(ev_mid, st) != hipSuccess)
         return set_hip_error(hipGetLastError(), "hipEventRecord");
 
-    dim3 rgrid((job.d / 4 + 3) / 4, job.batch), rblock(256);
+    dim3 rgrid = reduce_grid(job.d, job.batch), rblock(RED_WAVES * 64);
+    const int nch = job.bf16 ? job.d / 8 : 0;       // the streaming kernel's order of columns (fp32 rows: in order)
     if (job.multi) {
         if (job.bf16)
-            hipLaunchKernelGGL((ff_decode_reduce_kernel<true, true>), rgrid, rblock, 0, st, job.part, P, job.d, b2, b2m, job.y);
+            hipLaunchKernelGGL((ff_decode_reduce_kernel<true, true>), rgrid, rblock, 0, st, job.part, P, job.d, nch, b2, b2m, job.y);
         else
-            hipLaunchKernelGGL((ff_decode_reduce_kernel<false, true>), rgrid, rblock, 0, st, job.part, P, job.d, b2, b2m, job.y);
+            hipLaunchKernelGGL((ff_decode_reduce_kernel<false, true>), rgrid, rblock, 0, st, job.part, P, job.d, nch, b2, b2m, job.y);
     } else {
         if (job.bf16)
-            hipLaunchKernelGGL((ff_decode_reduce_kernel<true, false>), rgrid, rblock, 0, st, job.part, P, job.d, b2, b2m, job.y);
+            hipLaunchKernelGGL((ff_decode_reduce_kernel<true, false>), rgrid, rblock, 0, st, job.part, P, job.d, nch, b2, b2m, job.y);
         else
-            hipLaunchKernelGGL((ff_decode_reduce_kernel<false, false>), rgrid, rblock, 0, st, job.part, P, job.d, b2, b2m, job.y);
+            hipLaunchKernelGGL((ff_decode_reduce_kernel<false, false>), rgrid, rblock, 0, st, job.part, P, job.d, nch, b2, b2m, job.y);
     }
     rc = check_launch("ff_decode_reduce_kernel");
     if (rc == GRIFFIN_OK && ev_end && hipEventRecord(ev_end, st) != hipSuccess)

@@ -7,10 +7,12 @@
 // r_i^2 needs the whole row, so the scaling cannot finish inside one tile of the GEMM that
 // makes Z: the GEMM's epilogue leaves one sum-of-squares partial per (row, column tile), this
 // file turns them into the weights w_i = 1/r_i^2 (0 for an all-zero row) and streams Z once
-// more, coalesced along the neuron axis, to accumulate sum_i w_i Z_ij^2.  The token range of
-// every sequence is cut into `rc` chunks handled by different workgroups; a last small kernel
-// adds the chunk partials in a fixed order and takes the square root.  All of it is
-// bandwidth-bound: S*F fp32 reads.
+// more, coalesced along the neuron axis, to accumulate sum_i w_i Z_ij^2.  The tokens of every
+// sequence are cut into chunks of the same number of rows (so that prompts of different lengths
+// give workgroups of the same size: with the same number of chunks per prompt the long prompts'
+// workgroups ran on alone while most of the chip sat idle), handled by different workgroups; a last
+// small kernel adds a sequence's chunk partials in a fixed order and takes the square root.  All of
+// it is bandwidth-bound: S*F fp32 reads.
 #include "common.h"
 
 namespace griffin {
@@ -30,17 +32,29 @@ __global__ __launch_bounds__(256) void row_weight_kernel(const float *rowpart, i
         w[i] = acc > 0.0f ? 1.0f / acc : 0.0f;
 }
 
-// s2part[seq][chunk][j] = sum over the chunk's rows of w_i Z_ij^2
+// first chunk of every sequence in the global list of chunks (sequence b owns chunks first[b] .. first[b+1]-1)
+struct ChunkTable {
+    int32_t first[GRIFFIN_MAX_SEQS + 1];
+};
+
+// s2part[chunk][j] = sum over the chunk's rows of w_i Z_ij^2
 template <int VEC>
 __global__ __launch_bounds__(256) void col_stat_kernel(const float *Z, int64_t ldz, const float *w, int F,
-                                                       SeqTable seqs, int rc, float *s2part)
+                                                       SeqTable seqs, ChunkTable chunks, int rows_per_chunk, float *s2part)
 {
-    const int seq = blockIdx.z, chunk = blockIdx.y;
+    const int g = blockIdx.y;
     const int j = (blockIdx.x * 256 + threadIdx.x) * VEC;
     if (j >= F)
         return;
-    const int64_t lo0 = seqs.cu[seq], len = seqs.cu[seq + 1] - lo0;
-    const int64_t lo = lo0 + len * chunk / rc, hi = lo0 + len * (chunk + 1) / rc;
+    // the sequence this chunk belongs to: the last b with first[b] <= g (empty sequences own no chunk)
+    int b0 = 0, b1 = seqs.n;
+    while (b1 - b0 > 1) {
+        const int mid = (b0 + b1) >> 1;
+        if (chunks.first[mid] <= g) b0 = mid; else b1 = mid;
+    }
+    const int64_t lo = (int64_t)seqs.cu[b0] + (int64_t)(g - chunks.first[b0]) * rows_per_chunk;
+    const int64_t end = seqs.cu[b0 + 1];
+    const int64_t hi = lo + rows_per_chunk < end ? lo + rows_per_chunk : end;
     float acc[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v)
@@ -73,23 +87,24 @@ __global__ __launch_bounds__(256) void col_stat_kernel(const float *Z, int64_t l
             acc[v] = fmaf(zp[v] * zp[v], wi, acc[v]);
         zp += ldz;
     }
-    float *o = s2part + ((int64_t)seq * rc + chunk) * F + j;
+    float *o = s2part + (int64_t)g * F + j;
 #pragma unroll
     for (int v = 0; v < VEC; ++v)
         o[v] = acc[v];
 }
 
-// s[seq][j] = sqrt(sum_chunk s2part[seq][chunk][j]) in ascending chunk order
+// s[seq][j] = sqrt(sum of the sequence's chunk partials s2part[chunk][j]) in ascending chunk order
 // (one wavefront per 64 columns so that the few columns still fill the chip; eight loads in flight
-// per lane, added in chunk order)
-__global__ __launch_bounds__(64) void stat_finalize_kernel(const float *s2part, int rc, int F, float *s,
+// per lane, added in chunk order); a sequence without tokens has no chunk and gets s = 0
+__global__ __launch_bounds__(64) void stat_finalize_kernel(const float *s2part, ChunkTable chunks, int F, float *s,
                                                            float *s_out)
 {
     const int seq = blockIdx.y;
     const int j = blockIdx.x * 64 + threadIdx.x;
     if (j >= F)
         return;
-    const float *p = s2part + (int64_t)seq * rc * F + j;
+    const int c0 = chunks.first[seq], rc = chunks.first[seq + 1] - c0;
+    const float *p = s2part + (int64_t)c0 * F + j;
     float acc = 0.0f;
     int c = 0;
     for (; c + 8 <= rc; c += 8) {
@@ -124,22 +139,24 @@ __global__ __launch_bounds__(256) void stat_shared_kernel(const float *s, SeqTab
     sbar[j] = acc;
 }
 
-// number of token chunks per sequence: enough workgroups to fill the chip, at least ~16 rows each
-int stat_row_chunks(int64_t total_tokens, int32_t n_seqs, int32_t F)
+// Rows per chunk, the same for every sequence: enough chunks over all sequences to fill the chip
+// (about eight workgroups per CU), at least 16 rows each.
+int stat_rows_per_chunk(int64_t total_tokens, int32_t F)
 {
     const int64_t col_blocks = (F + 1023) / 1024;
-    int64_t want = 2048 / (col_blocks * (n_seqs > 0 ? n_seqs : 1));
-    const int64_t avg = total_tokens / (n_seqs > 0 ? n_seqs : 1);
-    if (want > avg / 16)
-        want = avg / 16;
-    if (want > 64)
-        want = 64;
-    return want < 1 ? 1 : (int)want;
+    const int64_t target = 2048 / col_blocks > 1 ? 2048 / col_blocks : 1;
+    const int64_t rows = (total_tokens + target - 1) / target;
+    return (int)(rows < 16 ? 16 : (rows > (1 << 20) ? (1 << 20) : rows));
+}
+
+// upper bound of the number of chunks of any split of total_tokens into n_seqs sequences
+int64_t stat_max_chunks(int64_t total_tokens, int32_t n_seqs, int32_t F)
+{
+    return total_tokens / stat_rows_per_chunk(total_tokens, F) + n_seqs;
 }
 
 int launch_stat(const float *Z, int64_t ldz, const float *rowpart, int nt, int64_t M, int32_t F,
-                const SeqTable &seqs, int rc, float *w, float *s2part, float *s, float *s_out,
-                hipStream_t st)
+                const SeqTable &seqs, float *w, float *s2part, float *s, float *s_out, hipStream_t st)
 {
     int rcode;
     if (M > 0) {
@@ -147,17 +164,28 @@ int launch_stat(const float *Z, int64_t ldz, const float *rowpart, int nt, int64
         if ((rcode = check_launch("row_weight_kernel")) != GRIFFIN_OK)
             return rcode;
     }
-    const bool vec4 = (F % 4 == 0) && (ldz % 4 == 0) && (((uintptr_t)Z & 15) == 0);
-    if (vec4) {
-        dim3 grid((F / 4 + 255) / 256, rc, seqs.n);
-        hipLaunchKernelGGL(col_stat_kernel<4>, grid, dim3(256), 0, st, Z, ldz, w, F, seqs, rc, s2part);
-    } else {
-        dim3 grid((F + 255) / 256, rc, seqs.n);
-        hipLaunchKernelGGL(col_stat_kernel<1>, grid, dim3(256), 0, st, Z, ldz, w, F, seqs, rc, s2part);
+    const int R = stat_rows_per_chunk(M, F);
+    ChunkTable chunks;
+    int32_t n_chunks = 0;
+    for (int b = 0; b < seqs.n; ++b) {
+        chunks.first[b] = n_chunks;
+        n_chunks += (int32_t)(((int64_t)seqs.cu[b + 1] - seqs.cu[b] + R - 1) / R);
     }
-    if ((rcode = check_launch("col_stat_kernel")) != GRIFFIN_OK)
-        return rcode;
-    hipLaunchKernelGGL(stat_finalize_kernel, dim3((F + 63) / 64, seqs.n), dim3(64), 0, st, s2part, rc, F, s, s_out);
+    for (int b = seqs.n; b <= GRIFFIN_MAX_SEQS; ++b)
+        chunks.first[b] = n_chunks;
+    if (n_chunks > 0) {
+        const bool vec4 = (F % 4 == 0) && (ldz % 4 == 0) && (((uintptr_t)Z & 15) == 0);
+        if (vec4) {
+            dim3 grid((F / 4 + 255) / 256, n_chunks);
+            hipLaunchKernelGGL(col_stat_kernel<4>, grid, dim3(256), 0, st, Z, ldz, w, F, seqs, chunks, R, s2part);
+        } else {
+            dim3 grid((F + 255) / 256, n_chunks);
+            hipLaunchKernelGGL(col_stat_kernel<1>, grid, dim3(256), 0, st, Z, ldz, w, F, seqs, chunks, R, s2part);
+        }
+        if ((rcode = check_launch("col_stat_kernel")) != GRIFFIN_OK)
+            return rcode;
+    }
+    hipLaunchKernelGGL(stat_finalize_kernel, dim3((F + 63) / 64, seqs.n), dim3(64), 0, st, s2part, chunks, F, s, s_out);
     return check_launch("stat_finalize_kernel");
 }
 

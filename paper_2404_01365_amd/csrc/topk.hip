@@ -6,12 +6,19 @@
 // largest key tau and how many entries equal to tau are still needed; an ordered compaction
 // (block-wide exclusive scan of per-thread counts over contiguous chunks) then writes every
 // index with key > tau plus the first `need` indices with key == tau, in ascending order.
-// D_ff <= 2^20 keys are re-read from L2 on every pass (98 KB for Gemma's 24576).
+// Rows of up to 32768 scores (every model shape in use) keep their keys in registers and a private
+// histogram per wavefront (topk_select_reg_kernel); longer rows keep them in LDS (up to 36864) or
+// re-read them from L2 on every pass (up to 2^20).
 #include "common.h"
 
 namespace griffin {
 
 constexpr int TOPK_THREADS = 1024;
+
+// (timing stamps of a lab build; nothing in the library)
+#ifndef TOPK_STAMP
+#define TOPK_STAMP(i_)
+#endif
 
 __device__ __forceinline__ uint32_t order_key(float f)
 {
@@ -66,6 +73,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(const float *
     const float *row = scores + (int64_t)blockIdx.x * n;
     int32_t *out = idx_out + (int64_t)blockIdx.x * k;
     const int tid = threadIdx.x;
+    TOPK_STAMP(0)
 
     if (CACHED) {
         int i = tid;
@@ -82,6 +90,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(const float *
             keys[i] = order_key(row[i]);
         __syncthreads();
     }
+    TOPK_STAMP(1)
 #define TOPK_KEY(i_) (CACHED ? keys[i_] : order_key(row[i_]))
 
     uint32_t prefix = 0, mask = 0, need = (uint32_t)k;
@@ -142,6 +151,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(const float *
         mask |= 255u << shift;
         need = sh_need;
         __syncthreads();
+        TOPK_STAMP(2 + pass)
     }
     const uint32_t tau = prefix;   // key of the k-th largest score; `need` entries equal to it are kept
 
@@ -157,6 +167,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(const float *
     uint32_t tot_gt, tot_eq;
     uint32_t p_gt = block_exclusive_scan(c_gt, sh_scan, tot_gt);
     uint32_t p_eq = block_exclusive_scan(c_eq, sh_scan, tot_eq);
+    TOPK_STAMP(6)
     for (int i = lo; i < hi; ++i) {
         const uint32_t key = TOPK_KEY(i);
         if (key > tau) {
@@ -168,11 +179,182 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(const float *
             ++p_eq;
         }
     }
+    TOPK_STAMP(7)
 #undef TOPK_KEY
+}
+
+// Rows of up to TOPK_REG_KEYS scores.  One CU does all the work of a row, so what counts is the number of
+// instructions per key and the latency chains between them (with the keys in LDS and one shared histogram
+// a pass over 11008 keys took 2-5 us: eleven dependent LDS reads per wave, and the sixteen waves' atomics
+// meeting in the few bins that the narrow range of the statistic fills):
+//   * the keys come in coalesced, pass through LDS once (padded by one word in 32 so that the chunk-strided
+//     read-back is free of bank conflicts) and then live in registers, a contiguous chunk of at most KPT per
+//     thread, so every pass is straight-line code;
+//   * every wavefront has its own 256-bin histogram: the lanes that share the digit of the wave's first
+//     candidate send one add with their count, the others add singly, and no add ever meets another wave's;
+//     the sixteen histograms are summed once per pass (more rounds of "first candidate's digit" per slot
+//     were tried and cost twice the time: the scalar loop is dearer than the adds it saves);
+//   * the two counts of the compaction ride in one packed scan, and the selected indices are put in order
+//     in LDS (where the keys were) and leave as coalesced stores.
+constexpr int TOPK_REG_KEYS = 32768;
+constexpr int TOPK_WAVES = TOPK_THREADS / 64;
+
+template <int KPT>
+__global__ __launch_bounds__(TOPK_THREADS) void topk_select_reg_kernel(const float *scores, int n, int k,
+                                                                       int32_t *idx_out)
+{
+    __shared__ uint32_t stage[TOPK_REG_KEYS + TOPK_REG_KEYS / 32];     // keys on the way in, indices on the way out
+    __shared__ uint32_t whist[TOPK_WAVES][256];
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t sh_digit, sh_need;
+    __shared__ uint32_t sh_scan[TOPK_WAVES];
+
+    const float *row = scores + (int64_t)blockIdx.x * n;
+    int32_t *out = idx_out + (int64_t)blockIdx.x * k;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    TOPK_STAMP(0)
+    {
+        int i = tid;
+        for (; i + 7 * TOPK_THREADS < n; i += 8 * TOPK_THREADS) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                v[u] = row[i + u * TOPK_THREADS];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int a = i + u * TOPK_THREADS;
+                stage[a + (a >> 5)] = order_key(v[u]);
+            }
+        }
+        for (; i < n; i += TOPK_THREADS)
+            stage[i + (i >> 5)] = order_key(row[i]);
+    }
+    __syncthreads();
+    // this thread's contiguous chunk of the row, in registers from here on
+    const int chunk = (n + TOPK_THREADS - 1) / TOPK_THREADS;       // <= KPT
+    const int lo = min(tid * chunk, n);
+    const int nv = min(chunk, n - lo);                             // keys this thread holds
+    uint32_t key[KPT];
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+        const int a = min(lo + j, n - 1);
+        key[j] = stage[a + (a >> 5)];
+    }
+    TOPK_STAMP(1)
+
+    uint32_t prefix = 0, mask = 0, need = (uint32_t)k;
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            whist[wave][lane * 4 + q] = 0;          // a wave's LDS accesses are performed in order: no barrier needed
+#pragma unroll
+        for (int j = 0; j < KPT; ++j) {
+            const bool cand = j < nv && (key[j] & mask) == prefix;
+            const uint64_t cmask = __ballot(cand);
+            if (cmask != 0) {
+                const uint32_t digit = (key[j] >> shift) & 255u;
+                const int leader = __builtin_ctzll(cmask);
+                const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)digit, leader);
+                const uint64_t same = __ballot(cand && digit == d0);
+                if (lane == leader)
+                    atomicAdd(&whist[wave][d0], (uint32_t)__builtin_popcountll(same));
+                else if (cand && digit != d0)
+                    atomicAdd(&whist[wave][digit], 1u);
+            }
+        }
+        __syncthreads();
+        if (tid < 256) {
+            uint32_t t = 0;
+#pragma unroll
+            for (int w = 0; w < TOPK_WAVES; ++w)
+                t += whist[w][tid];
+            hist[tid] = t;
+        }
+        __syncthreads();
+        // the digit of the k-th largest: the one bin b with S[b] >= need > S[b+1], S[b] = sum of the
+        // bins b' >= b.  One wavefront: lane l owns bins 4l .. 4l+3, suffix sums across lanes by shuffles.
+        if (tid < 64) {
+            const uint32_t h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2], h3 = hist[4 * tid + 3];
+            const uint32_t loc = h0 + h1 + h2 + h3;
+            uint32_t suf = loc;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t t = __shfl_down(suf, off, 64);
+                if (tid + off < 64)
+                    suf += t;
+            }
+            const uint32_t s4 = suf - loc, s3 = s4 + h3, s2 = s3 + h2, s1 = s2 + h1, s0 = s1 + h0;
+            if (s0 >= need && s4 < need) {
+                uint32_t dg, above;
+                if (s3 >= need) { dg = 3; above = s4; }
+                else if (s2 >= need) { dg = 2; above = s3; }
+                else if (s1 >= need) { dg = 1; above = s2; }
+                else { dg = 0; above = s1; }
+                sh_digit = 4u * tid + dg;
+                sh_need = need - above;
+            }
+        }
+        __syncthreads();
+        prefix |= sh_digit << shift;
+        mask |= 255u << shift;
+        need = sh_need;
+        TOPK_STAMP(2 + pass)
+    }
+    const uint32_t tau = prefix;   // key of the k-th largest score; `need` entries equal to it are kept
+
+    // ordered compaction: both counts in one packed scan (each total is at most 32768: 16 bits apiece)
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int j = 0; j < KPT; ++j)
+        if (j < nv)
+            cnt += (key[j] > tau ? 1u : 0u) + (key[j] == tau ? 0x10000u : 0u);
+    uint32_t inc = cnt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t t = __shfl_up(inc, off, 64);
+        if (lane >= off)
+            inc += t;
+    }
+    if (lane == 63)
+        sh_scan[wave] = inc;
+    __syncthreads();
+    uint32_t base = 0;
+#pragma unroll
+    for (int w = 0; w < TOPK_WAVES; ++w)
+        base += w < wave ? sh_scan[w] : 0u;
+    const uint32_t excl = base + inc - cnt;
+    uint32_t p_gt = excl & 0xFFFFu, p_eq = excl >> 16;
+    TOPK_STAMP(6)
+    // the keys are all in registers: the staging area now collects the selected indices in order
+    // (a key above tau and a kept key equal to tau land at the same formula: p_gt + min(p_eq, need))
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+        const bool gt = j < nv && key[j] > tau, eq = j < nv && key[j] == tau;
+        if (gt || (eq && p_eq < need))
+            stage[p_gt + min(p_eq, need)] = (uint32_t)(lo + j);
+        p_gt += gt ? 1u : 0u;
+        p_eq += eq ? 1u : 0u;
+    }
+    __syncthreads();
+    for (int i = tid; i < k; i += TOPK_THREADS)
+        out[i] = (int32_t)stage[i];
+    TOPK_STAMP(7)
 }
 
 int launch_topk(const float *scores, int32_t n_rows, int32_t n, int32_t k, int32_t *idx, hipStream_t st)
 {
+    if (n <= TOPK_REG_KEYS) {
+        const int chunk = (n + TOPK_THREADS - 1) / TOPK_THREADS;
+        dim3 grid(n_rows), block(TOPK_THREADS);
+        if (chunk <= 4) hipLaunchKernelGGL(topk_select_reg_kernel<4>, grid, block, 0, st, scores, n, k, idx);
+        else if (chunk <= 8) hipLaunchKernelGGL(topk_select_reg_kernel<8>, grid, block, 0, st, scores, n, k, idx);
+        else if (chunk <= 12) hipLaunchKernelGGL(topk_select_reg_kernel<12>, grid, block, 0, st, scores, n, k, idx);
+        else if (chunk <= 16) hipLaunchKernelGGL(topk_select_reg_kernel<16>, grid, block, 0, st, scores, n, k, idx);
+        else if (chunk <= 24) hipLaunchKernelGGL(topk_select_reg_kernel<24>, grid, block, 0, st, scores, n, k, idx);
+        else hipLaunchKernelGGL(topk_select_reg_kernel<32>, grid, block, 0, st, scores, n, k, idx);
+        return check_launch("topk_select_reg_kernel");
+    }
     if (n <= TOPK_CACHE_KEYS)
         hipLaunchKernelGGL(topk_select_kernel<true>, dim3(n_rows), dim3(TOPK_THREADS), 0, st, scores, n, k, idx);
     else
