@@ -140,8 +140,10 @@ int griffin_weight_norm_score(const griffin_layer *L, float *score_out, void *st
  * from the remaining neurons without replacement with probability proportional to s_j
  * (k_top = 0: "sampling"; k_top = k/2: "top-k + sampling"; k_top = k: plain top-k).  The draw is
  * the exponential-clocks form of weighted sampling without replacement: neuron j rings at
- * e_j / s_j and the earliest rings win, decided on q_j = s_j / e_j in single precision (capped
- * at 1e38), largest first, ties to the lower index; a zero weight never beats a positive one.
+ * e_j / s_j and the earliest rings win, decided on q_j = s_j / e_j, largest first, ties to the
+ * lower index; a zero weight never beats a positive one.  The device forms q_j in single precision
+ * (values above 1e38 count as 1e38), so two neurons whose quotients differ by less than a few
+ * units of 1e-7 relative may swap against an exact evaluation.
  *   s [n] fp32 >= 0 (the statistic of Eq. 6, or s_bar of Eq. 7)
  *   e [n] fp32 > 0: one unit-rate exponential variate per neuron, drawn by the caller (the
  *     library draws no random numbers)

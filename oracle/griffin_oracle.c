@@ -256,7 +256,7 @@ int oracle_weight_norm_score(int64_t n, int64_t d, const double *Wg, const doubl
 }
 
 typedef struct {
-    float q;
+    double q;
     int32_t j;
 } oracle_qkey;
 
@@ -276,9 +276,9 @@ static int oracle_cmp_q_desc(const void *pa, const void *pb)
  * the exponential-clocks form of weighted sampling without replacement: neuron j rings at time
  * e_j / s_j, with e_j a unit-rate exponential variate supplied by the caller (the method's
  * random numbers are inputs), and the earliest k - k_top rings win.  The winner of "earliest
- * ring" is decided on q_j = s_j / e_j, largest first, computed in IEEE single precision (the
- * precision the device decides in), capped at 1e38; ties go to the lowest index; s_j = 0
- * never beats a positive weight.  The set is returned ascending.
+ * ring" is decided on q_j = s_j / e_j, largest first, in double precision like everything else
+ * here; ties go to the lowest index; s_j = 0 (q_j = 0) never beats a positive weight.  The set
+ * is returned ascending.
  */
 int oracle_select_sampled(int64_t F, const double *s, const float *e, int64_t k, int64_t k_top, int32_t *idx)
 {
@@ -300,10 +300,7 @@ int oracle_select_sampled(int64_t F, const double *s, const float *e, int64_t k,
     for (int64_t j = 0; j < F; ++j) {
         if (taken[j])
             continue;
-        float q = (float)s[j] / e[j];
-        if (q > 1.0e38f)
-            q = 1.0e38f;
-        keys[m].q = q;
+        keys[m].q = s[j] / (double)e[j];
         keys[m].j = (int32_t)j;
         ++m;
     }

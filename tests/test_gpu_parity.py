@@ -614,17 +614,53 @@ def test_weight_norm_score_matches_oracle(dtype, d, F, gated):
         np.testing.assert_array_equal(idx.cpu().numpy()[0], oracle.topk(ref, k))
 
 
+def open_sampling_margin(s, e, k, k_top, gap=1e-4, max_iter=50):
+    """The device decides the draw on q = s / e in single precision, the oracle in double: the sets agree
+    bit for bit where no quotient sits within `gap` (relative; a single-precision quotient is off by 6e-8)
+    of the value that separates drawn from not drawn, exact ties aside (equal operands give equal quotients
+    in either precision and go to the lower index on both sides).  Clocks e of neurons that sit too close
+    are moved by 0.3 % until that holds.  Uses the oracle's own top-k for the part that is not drawn."""
+    e = e.copy()
+    m = k - k_top
+    if m <= 0:
+        return e
+    rest = np.setdiff1d(np.arange(s.shape[0]), oracle.topk(s, k_top) if k_top > 0 else np.empty(0, dtype=np.int64))
+    if m >= rest.shape[0]:
+        return e
+    for _ in range(max_iter):
+        q = s[rest].astype(np.float64) / e[rest].astype(np.float64)
+        order = np.argsort(-q, kind="stable")
+        a, b = q[order[m - 1]], q[order[m]]              # last one drawn, first one left
+        if a == 0.0:
+            return e                                     # only zero weights left to draw from: decided by index alone
+        near = np.zeros(q.shape[0], dtype=bool)
+        for v in {a, b}:
+            if v > 0.0:
+                near |= (np.abs(q - v) < gap * v) & (q != v)
+        if a != b and (a - b) < gap * a:
+            near[order[m]] = True
+        if not near.any():
+            return e
+        up = q[near] >= a                                 # drawn ones ring a little earlier, the others later
+        e[rest[near]] = (e[rest[near]] * np.where(up, np.float32(0.997), np.float32(1.003))).astype(np.float32)
+    raise RuntimeError("sampling margin did not open")
+
+
 @pytest.mark.parametrize("n,k", [(11008, 5504), (1000, 1), (257, 256), (64, 64)])
-def test_select_sampled_matches_oracle_bitwise(n, k):
+def test_select_sampled_matches_oracle(n, k):
+    """Appendix B: the oracle decides on q = s / e in double precision, the device in single; the inputs keep
+    every quotient clear of the deciding value, so the sets must agree bit for bit."""
     rng = np.random.default_rng(n + k)
     s = (rng.random(n) ** 4).astype(np.float32)            # concentrated like the statistic (Appendix A)
     s[rng.choice(n, n // 10, replace=False)] = 0.0          # neurons that never fired
-    e = rng.exponential(size=n).astype(np.float32)
-    e = np.maximum(e, np.float32(1e-6))
-    e[: n // 8] = np.float32(0.5)                           # equal clocks: ties in q wherever s ties too
+    e0 = rng.exponential(size=n).astype(np.float32)
+    e0 = np.maximum(e0, np.float32(1e-6))
+    e0[: n // 8] = np.float32(0.5)                          # equal clocks: exact ties in q wherever s ties too
     s[: n // 16] = np.float32(0.25)
-    sd, ed = torch.from_numpy(s).cuda(), torch.from_numpy(e).cuda()
+    sd = torch.from_numpy(s).cuda()
     for k_top in sorted({0, k // 2, k}):
+        e = open_sampling_margin(s, e0, k, k_top)
+        ed = torch.from_numpy(e).cuda()
         ws = workspace(G.griffin_select_sampled_workspace_bytes(n, k_top))
         idx = torch.full((k,), -1, dtype=torch.int32, device="cuda")
         G.griffin_select_sampled(sd, ed, k, k_top, idx, workspace=ws)
