@@ -282,7 +282,10 @@ int griffin_prompt_phase(const griffin_layer *L, const void *W2p, int64_t ldw, c
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Instrumentation for measurement (the generation phase is where the time goes, Section 5.2):
+ * MEASUREMENT ONLY -- not part of the method's interface and the one entry point that keeps state
+ * between calls (a one-shot, per-thread note of three event handles; every other entry point is
+ * stateless).  It exists so that a benchmark can time the kernels of a decode call on the stream
+ * they run on (the generation phase is where the time goes, Section 5.2):
  * the next griffin_ff_decode* call made by this thread records, on that call's stream,
  * event_begin just before its weight-streaming kernel, event_mid between that kernel and the
  * small kernel that sums the partial rows, and event_end after the latter; then it forgets

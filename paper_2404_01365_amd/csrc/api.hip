@@ -75,7 +75,7 @@ static int fill_seq_table(const int32_t *cu, int32_t n_seqs, SeqTable &t, int64_
 }
 
 struct PrefillPlan {
-    size_t off_z, off_rowpart, off_w, off_s2part, off_s, total;
+    size_t off_z, off_rowpart, off_s2part, off_s, total;
     int nt;
 };
 
@@ -89,8 +89,6 @@ static PrefillPlan plan_prefill(const griffin_layer &L, int64_t total_tokens, in
         off += align256((size_t)total_tokens * L.n * sizeof(float));
     pl.off_rowpart = off;
     off += align256((size_t)total_tokens * pl.nt * sizeof(float));
-    pl.off_w = off;
-    off += align256((size_t)total_tokens * sizeof(float));
     pl.off_s2part = off;
     off += align256((size_t)stat_max_chunks(total_tokens, n_seqs, L.n) * L.n * sizeof(float));
     pl.off_s = off;
@@ -170,14 +168,13 @@ int griffin_prefill_select(const griffin_layer *L, const void *X, int64_t ldx,
     float *Z = Z_out ? Z_out : (float *)(ws + pl.off_z);
     const int64_t zld = Z_out ? ldz : L->n;
     float *rowpart = (float *)(ws + pl.off_rowpart);
-    float *w = (float *)(ws + pl.off_w);
     float *s2part = (float *)(ws + pl.off_s2part);
     float *s = (float *)(ws + pl.off_s);
 
     int32_t nt = 0;
     if ((rc = launch_ff1(*L, X, ldx, total, Z, zld, rowpart, &nt, st)) != GRIFFIN_OK)
         return rc;
-    if ((rc = launch_stat(Z, zld, rowpart, nt, total, L->n, seqs, w, s2part, s, s_out, st)) != GRIFFIN_OK)
+    if ((rc = launch_stat(Z, zld, rowpart, nt, total, L->n, seqs, s2part, s, s_out, st)) != GRIFFIN_OK)
         return rc;
     return launch_topk(s, n_seqs, L->n, k, idx_out, st);
 }
@@ -330,7 +327,6 @@ int griffin_prompt_phase(const griffin_layer *L, const void *W2p, int64_t ldw, c
     char *ws = (char *)workspace;
     float *Z = (float *)(ws + pl.off_z);
     float *rowpart = (float *)(ws + pl.off_rowpart);
-    float *w = (float *)(ws + pl.off_w);
     float *s2part = (float *)(ws + pl.off_s2part);
     float *s = (float *)(ws + pl.off_s);
     float *ws2 = (float *)(ws + pl.total);
@@ -342,7 +338,7 @@ int griffin_prompt_phase(const griffin_layer *L, const void *W2p, int64_t ldw, c
     int32_t nt = 0;
     if ((rc = launch_ff1(*L, X, ldx, total, Z, L->n, rowpart, &nt, st, fuse ? (uint16_t *)ws2 : nullptr, L->n)) != GRIFFIN_OK)
         return rc;
-    if ((rc = launch_stat(Z, L->n, rowpart, nt, total, L->n, seqs, w, s2part, s, s_out, st)) != GRIFFIN_OK)
+    if ((rc = launch_stat(Z, L->n, rowpart, nt, total, L->n, seqs, s2part, s, s_out, st)) != GRIFFIN_OK)
         return rc;
     if ((rc = launch_topk(s, n_seqs, L->n, k, idx_out, st)) != GRIFFIN_OK)
         return rc;

@@ -116,7 +116,7 @@ int launch_ff1(const griffin_layer &L, const void *X, int64_t ldx, int64_t M, fl
 bool ff1_can_write_zb(const griffin_layer &L, int64_t ldx, const float *Z, int64_t ldz);
 int ff1_ntiles(const griffin_layer &L);
 int launch_stat(const float *Z, int64_t ldz, const float *rowpart, int nt, int64_t M, int32_t F,
-                const SeqTable &seqs, float *w, float *s2part, float *s, float *s_out, hipStream_t st);
+                const SeqTable &seqs, float *s2part, float *s, float *s_out, hipStream_t st);
 int64_t stat_max_chunks(int64_t total_tokens, int32_t n_seqs, int32_t F);
 int launch_topk(const float *scores, int32_t n_rows, int32_t n, int32_t k, int32_t *idx, hipStream_t st);
 int launch_stat_shared(const float *s, const SeqTable &seqs, int32_t n, float *sbar, hipStream_t st);

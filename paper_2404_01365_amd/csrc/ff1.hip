@@ -16,6 +16,8 @@
 // fp32: a plain LDS-tiled FMA kernel (64x64 tile); exists for exactness tests and small cases.
 #include "common.h"
 
+#include <atomic>
+
 namespace griffin {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -813,15 +815,23 @@ int ff1_ntiles(const griffin_layer &L)
     return (L.n + bn - 1) / bn;
 }
 
-// one workgroup per CU (a multiple of 8, so that every XCD gets the same number), fewer if there are fewer tiles
+// one workgroup per CU (a multiple of 8, so that every XCD gets the same number), fewer if there are fewer tiles.
+// The CU count is asked of the current device at every launch's first use on that device and kept per device.
 static int ff1_grid(int nblk)
 {
-    static int cus = 0;
+    constexpr int MAX_DEV = 64;
+    static std::atomic<int> cus_of[MAX_DEV];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV)
+        dev = -1;
+    int cus = dev >= 0 ? cus_of[dev].load(std::memory_order_relaxed) : 0;
     if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8)
+        int n = 0;
+        if (dev < 0 || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8)
             n = 256;
         cus = n & ~7;
+        if (dev >= 0)
+            cus_of[dev].store(cus, std::memory_order_relaxed);
     }
     const int want = ((nblk + 7) / 8) * 8;
     return want < cus ? want : cus;

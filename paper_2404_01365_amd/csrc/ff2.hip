@@ -4,12 +4,18 @@
 //
 // A dense contraction (2*S*D_ff*d flop), so bf16 blocks run on the matrix cores.  W_2 is taken
 // in the paper's own layout, W2p[d][D_ff] (row c = output feature c), which makes both operands
-// K-contiguous ("NT"), exactly the shape of the first GEMM.  Z is fp32 in memory: it is
-// converted to bf16 on its way through registers into LDS (so the loads are register-staged,
-// 16-byte, double-buffered, BK = 64), W2p tiles are staged the same way; a 256-token x
-// 128-feature workgroup tile, 4 waves of 128 x 64, v_mfma_f32_32x32x16_bf16, XOR-swizzled LDS
-// rows, operand fragments double-buffered over k-steps.  Shapes the tiles cannot take
-// (D_ff not a multiple of 8, fp32 blocks) go through a plain fp32 kernel.
+// K-contiguous ("NT"), exactly the shape of the first GEMM.  Three routes, chosen in launch_ff2:
+//   * the usual one (D_ff in whole 64-element k-tiles): a bf16 copy of Z (made here by
+//     ff2_z_to_bf16_kernel, or already left by the first GEMM's epilogue) goes through the
+//     direct-to-LDS kernel of the first GEMM in its plain mode (256-token x 256-feature tiles,
+//     launch_gemm_nt_partials), the long contraction over D_ff cut into ranges that each write
+//     an fp32 slab, and ff2_split_sum_kernel adds the slabs in a fixed order, adds b_2 and
+//     converts;
+//   * D_ff not in whole k-tiles: the register-staged kernel of this file (fp32 Z converted to
+//     bf16 on its way through registers into LDS, 16-byte loads, double-buffered, BK = 64, a
+//     256-token x 128-feature tile, 4 waves of 128 x 64, v_mfma_f32_32x32x16_bf16, XOR-swizzled
+//     LDS rows), with the same ranges and the same sum;
+//   * shapes the tiles cannot take (D_ff not a multiple of 8, fp32 blocks): a plain fp32 kernel.
 #include "common.h"
 
 namespace griffin {

@@ -5,8 +5,8 @@
 //   s_j   = sqrt( sum_{i in sequence} Z_ij^2 / r_i^2 )
 //
 // r_i^2 needs the whole row, so the scaling cannot finish inside one tile of the GEMM that
-// makes Z: the GEMM's epilogue leaves one sum-of-squares partial per (row, column tile), this
-// file turns them into the weights w_i = 1/r_i^2 (0 for an all-zero row) and streams Z once
+// makes Z: the GEMM's epilogue leaves one sum-of-squares partial per (row, column tile), the
+// kernel here turns them into the weights w_i = 1/r_i^2 (0 for an all-zero row) and streams Z once
 // more, coalesced along the neuron axis, to accumulate sum_i w_i Z_ij^2.  The tokens of every
 // sequence are cut into chunks of the same number of rows (so that prompts of different lengths
 // give workgroups of the same size: with the same number of chunks per prompt the long prompts'
@@ -17,35 +17,27 @@
 
 namespace griffin {
 
-// w[i] = 1 / sum_t rowpart[i][t]; one wavefront per row
-__global__ __launch_bounds__(256) void row_weight_kernel(const float *rowpart, int nt, int64_t M, float *w)
-{
-    const int lane = threadIdx.x & 63;
-    const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (i >= M)
-        return;
-    float acc = 0.0f;
-    for (int t = lane; t < nt; t += 64)
-        acc += rowpart[i * nt + t];
-    acc = wave_sum(acc);
-    if (lane == 0)
-        w[i] = acc > 0.0f ? 1.0f / acc : 0.0f;
-}
-
 // first chunk of every sequence in the global list of chunks (sequence b owns chunks first[b] .. first[b+1]-1)
 struct ChunkTable {
     int32_t first[GRIFFIN_MAX_SEQS + 1];
 };
 
-// s2part[chunk][j] = sum over the chunk's rows of w_i Z_ij^2
+// s2part[chunk][j] = sum over the chunk's rows of w_i Z_ij^2, w_i = 1 / sum_t rowpart[i][t] (0 for an all-zero
+// row).  A workgroup first turns the row partials of its own rows into weights (one wavefront per row: lanes
+// over the column tiles, then a wave sum; every column block of a chunk repeats this for the same few rows,
+// which is far cheaper than a kernel of its own in front of this one) and keeps them in LDS.
+constexpr int STAT_ROWS_LDS = 256;
+
 template <int VEC>
-__global__ __launch_bounds__(256) void col_stat_kernel(const float *Z, int64_t ldz, const float *w, int F,
+__global__ __launch_bounds__(256) void col_stat_kernel(const float *Z, int64_t ldz, const float *rowpart, int nt, int F,
                                                        SeqTable seqs, ChunkTable chunks, int rows_per_chunk, float *s2part)
 {
+    __shared__ float w_s[STAT_ROWS_LDS];
     const int g = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = (blockIdx.x * 256 + threadIdx.x) * VEC;
-    if (j >= F)
-        return;
+    const bool live = j < F;
+    const int jc = live ? j : 0;              // columns past the end: loads stay in bounds, nothing is stored
     // the sequence this chunk belongs to: the last b with first[b] <= g (empty sequences own no chunk)
     int b0 = 0, b1 = seqs.n;
     while (b1 - b0 > 1) {
@@ -59,38 +51,54 @@ __global__ __launch_bounds__(256) void col_stat_kernel(const float *Z, int64_t l
 #pragma unroll
     for (int v = 0; v < VEC; ++v)
         acc[v] = 0.0f;
-    const float *zp = Z + lo * ldz + j;
-    int64_t i = lo;
-    for (; i + 4 <= hi; i += 4) {
-        float zz[4][VEC], ww[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            ww[r] = w[i + r];
-            if (VEC == 4) {
-                float4 t = *(const float4 *)(zp + r * ldz);
-                zz[r][0] = t.x; zz[r][1 % VEC] = t.y; zz[r][2 % VEC] = t.z; zz[r][3 % VEC] = t.w;
-            } else {
-                zz[r][0] = zp[r * ldz];
-            }
+    for (int64_t r0 = lo; r0 < hi; r0 += STAT_ROWS_LDS) {
+        const int nr = (int)(hi - r0 < STAT_ROWS_LDS ? hi - r0 : STAT_ROWS_LDS);
+        __syncthreads();                       // the weights of the block before have been used
+        for (int r = wave; r < nr; r += 4) {
+            const float *rp = rowpart + (r0 + r) * nt;
+            float a = 0.0f;
+            for (int t = lane; t < nt; t += 64)
+                a += rp[t];
+            a = wave_sum(a);
+            if (lane == 0)
+                w_s[r] = a > 0.0f ? 1.0f / a : 0.0f;
         }
+        __syncthreads();
+        const float *zp = Z + r0 * ldz + jc;
+        int i = 0;
+        for (; i + 4 <= nr; i += 4) {
+            float zz[4][VEC], ww[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+            for (int r = 0; r < 4; ++r) {
+                ww[r] = w_s[i + r];
+                if (VEC == 4) {
+                    float4 t = *(const float4 *)(zp + r * ldz);
+                    zz[r][0] = t.x; zz[r][1 % VEC] = t.y; zz[r][2 % VEC] = t.z; zz[r][3 % VEC] = t.w;
+                } else {
+                    zz[r][0] = zp[r * ldz];
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v)
+                    acc[v] = fmaf(zz[r][v] * zz[r][v], ww[r], acc[v]);
+            zp += 4 * ldz;
+        }
+        for (; i < nr; ++i) {
+            const float wi = w_s[i];
 #pragma unroll
             for (int v = 0; v < VEC; ++v)
-                acc[v] = fmaf(zz[r][v] * zz[r][v], ww[r], acc[v]);
-        zp += 4 * ldz;
+                acc[v] = fmaf(zp[v] * zp[v], wi, acc[v]);
+            zp += ldz;
+        }
     }
-    for (; i < hi; ++i) {
-        const float wi = w[i];
+    if (live) {
+        float *o = s2part + (int64_t)g * F + j;
 #pragma unroll
         for (int v = 0; v < VEC; ++v)
-            acc[v] = fmaf(zp[v] * zp[v], wi, acc[v]);
-        zp += ldz;
+            o[v] = acc[v];
     }
-    float *o = s2part + (int64_t)g * F + j;
-#pragma unroll
-    for (int v = 0; v < VEC; ++v)
-        o[v] = acc[v];
 }
 
 // s[seq][j] = sqrt(sum of the sequence's chunk partials s2part[chunk][j]) in ascending chunk order
@@ -156,14 +164,9 @@ int64_t stat_max_chunks(int64_t total_tokens, int32_t n_seqs, int32_t F)
 }
 
 int launch_stat(const float *Z, int64_t ldz, const float *rowpart, int nt, int64_t M, int32_t F,
-                const SeqTable &seqs, float *w, float *s2part, float *s, float *s_out, hipStream_t st)
+                const SeqTable &seqs, float *s2part, float *s, float *s_out, hipStream_t st)
 {
     int rcode;
-    if (M > 0) {
-        hipLaunchKernelGGL(row_weight_kernel, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st, rowpart, nt, M, w);
-        if ((rcode = check_launch("row_weight_kernel")) != GRIFFIN_OK)
-            return rcode;
-    }
     const int R = stat_rows_per_chunk(M, F);
     ChunkTable chunks;
     int32_t n_chunks = 0;
@@ -177,10 +180,10 @@ int launch_stat(const float *Z, int64_t ldz, const float *rowpart, int nt, int64
         const bool vec4 = (F % 4 == 0) && (ldz % 4 == 0) && (((uintptr_t)Z & 15) == 0);
         if (vec4) {
             dim3 grid((F / 4 + 255) / 256, n_chunks);
-            hipLaunchKernelGGL(col_stat_kernel<4>, grid, dim3(256), 0, st, Z, ldz, w, F, seqs, chunks, R, s2part);
+            hipLaunchKernelGGL(col_stat_kernel<4>, grid, dim3(256), 0, st, Z, ldz, rowpart, nt, F, seqs, chunks, R, s2part);
         } else {
             dim3 grid((F + 255) / 256, n_chunks);
-            hipLaunchKernelGGL(col_stat_kernel<1>, grid, dim3(256), 0, st, Z, ldz, w, F, seqs, chunks, R, s2part);
+            hipLaunchKernelGGL(col_stat_kernel<1>, grid, dim3(256), 0, st, Z, ldz, rowpart, nt, F, seqs, chunks, R, s2part);
         }
         if ((rcode = check_launch("col_stat_kernel")) != GRIFFIN_OK)
             return rcode;
