@@ -709,6 +709,29 @@ def test_prefill_takes_the_maximum_number_of_sequences():
             assert np.min(s[b][idx[b]]) >= np.max(np.delete(s[b], idx[b])) - 1e-12
 
 
+def test_statistic_with_many_short_prompts_beside_a_long_one():
+    """255 prompts of 8 tokens and one of 9000 in one call: few chunks are left for the long prompt, each of
+    them holds more rows than a workgroup keeps weights for at a time (its second block of rows), and every
+    short prompt is one partial chunk.  Z and s are compared for every sequence (Section 4.1, Eq. 6)."""
+    dtype, d, F, k, act = synth.DT_BF16, 64, 7168, 3000, synth.ACT_SILU
+    lens = [8] * 255 + [9000]
+    c = synth.small_case(2024, d, F, sum(lens), dtype)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    L, _ = dev_layer(c["Wg"], c["W1"], c["W2"], act, dtype)
+    idx, s, Z = run_prefill(L, to_dev(c["X"], dtype), cu, k)
+    Z_ref = oracle.ff1(c["X"], c["Wg"], c["W1"], act)
+    assert max_rel(Z, Z_ref) <= TOL_Z
+    for b in range(len(lens)):
+        s_ref = oracle.stat(Z_ref[cu[b]:cu[b + 1]])
+        assert np.max(np.abs(s[b] - s_ref)) <= TOL_S * np.max(s_ref), b
+        assert np.sum(s[b] ** 2) == pytest.approx(lens[b], rel=1e-4)
+        if boundary_report(s_ref, k)[0] > 1e-3:
+            np.testing.assert_array_equal(idx[b], oracle.topk(s_ref, k))
+        else:       # the boundary is too tight to pin the set: what is selected must still be a top-k of the device's own s
+            assert np.all(np.diff(idx[b]) > 0)
+            assert np.min(s[b][idx[b]]) >= np.max(np.delete(s[b], idx[b])) - 1e-12
+
+
 def test_decode_takes_the_maximum_batch():
     """GRIFFIN_MAX_BATCH rows: per-row index lists, per-row compact blocks, one shared block."""
     dtype, d, n, k, B = synth.DT_BF16, 512, 200, 64, G.MAX_BATCH
