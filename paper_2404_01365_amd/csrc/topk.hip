@@ -16,10 +16,6 @@ namespace griffin {
 
 constexpr int TOPK_THREADS = 1024;
 
-// (timing stamps of a lab build; nothing in the library)
-#ifndef TOPK_STAMP
-#define TOPK_STAMP(i_)
-#endif
 
 __device__ __forceinline__ uint32_t order_key(float f)
 {
@@ -74,7 +70,6 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(const float *
     const float *row = scores + (int64_t)blockIdx.x * n;
     int32_t *out = idx_out + (int64_t)blockIdx.x * k;
     const int tid = threadIdx.x;
-    TOPK_STAMP(0)
 
     if (CACHED) {
         int i = tid;
@@ -91,7 +86,6 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(const float *
             keys[i] = order_key(row[i]);
         __syncthreads();
     }
-    TOPK_STAMP(1)
 #define TOPK_KEY(i_) (CACHED ? keys[i_] : order_key(row[i_]))
 
     uint32_t prefix = 0, mask = 0, need = (uint32_t)k;
@@ -152,7 +146,6 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(const float *
         mask |= 255u << shift;
         need = sh_need;
         __syncthreads();
-        TOPK_STAMP(2 + pass)
     }
     const uint32_t tau = prefix;   // key of the k-th largest score; `need` entries equal to it are kept
 
@@ -168,7 +161,6 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(const float *
     uint32_t tot_gt, tot_eq;
     uint32_t p_gt = block_exclusive_scan(c_gt, sh_scan, tot_gt);
     uint32_t p_eq = block_exclusive_scan(c_eq, sh_scan, tot_eq);
-    TOPK_STAMP(6)
     for (int i = lo; i < hi; ++i) {
         const uint32_t key = TOPK_KEY(i);
         if (key > tau) {
@@ -180,7 +172,6 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(const float *
             ++p_eq;
         }
     }
-    TOPK_STAMP(7)
 #undef TOPK_KEY
 }
 
@@ -215,7 +206,6 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_reg_kernel(const flo
     const float *row = scores + (int64_t)blockIdx.x * n;
     int32_t *out = idx_out + (int64_t)blockIdx.x * k;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    TOPK_STAMP(0)
     {
         int i = tid;
         for (; i + 7 * TOPK_THREADS < n; i += 8 * TOPK_THREADS) {
@@ -243,7 +233,6 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_reg_kernel(const flo
         const int a = min(lo + j, n - 1);
         key[j] = stage[a + (a >> 5)];
     }
-    TOPK_STAMP(1)
 
     // ---- the range of the keys: the select works on rel = key - kmin, whose top eight bits BELOW the highest
     // set bit of (kmax - kmin) spread the row over all 256 bins of the first pass, whatever exponent the
@@ -361,7 +350,6 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_reg_kernel(const flo
     TOPK_FIND_BIN(true)
     uint32_t tau = sh_digit << shift0;          // rel of the k-th largest, low bits still to come
     need = sh_need;
-    TOPK_STAMP(2)
 
     if (shift0 > 0) {
         // ---- the keys of that bin (a few per cent of the row) go into a list in LDS (the staging area is free:
@@ -373,7 +361,6 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_reg_kernel(const flo
                 stage[atomicAdd(&sh_ncand, 1u)] = key[j] & low_mask;
         __syncthreads();
         const int ncand = (int)sh_ncand;
-        TOPK_STAMP(3)
         uint32_t lprefix = 0;                   // the digits found so far, as the high bits of the low part
         for (int bits = shift0; bits > 0;) {
             const int w = bits < 8 ? bits : 8, sh = bits - w;
@@ -393,7 +380,6 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_reg_kernel(const flo
         __syncthreads();                        // the list has been read for the last time: the area is written again below
     }
 #undef TOPK_FIND_BIN
-    TOPK_STAMP(5)
     // tau: rel of the k-th largest score; `need` entries equal to it are kept
 
     // ordered compaction: both counts in one packed scan (each total is at most 32768: 16 bits apiece)
@@ -418,7 +404,6 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_reg_kernel(const flo
         base += w < wave ? sh_scan[w] : 0u;
     const uint32_t excl = base + inc - cnt;
     uint32_t p_gt = excl & 0xFFFFu, p_eq = excl >> 16;
-    TOPK_STAMP(6)
     // the keys are all in registers: the staging area now collects the selected indices in order
     // (a key above tau and a kept key equal to tau land at the same formula: p_gt + min(p_eq, need))
 #pragma unroll
@@ -432,7 +417,6 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_reg_kernel(const flo
     __syncthreads();
     for (int i = tid; i < k; i += TOPK_THREADS)
         out[i] = (int32_t)stage[i];
-    TOPK_STAMP(7)
 }
 
 int launch_topk(const float *scores, int32_t n_rows, int32_t n, int32_t k, int32_t *idx, hipStream_t st)
