@@ -63,3 +63,40 @@ def test_decode_static_rejects_what_does_not_fit():
     assert G.lib.griffin_ff_decode_static(ctypes.byref(L), x.data_ptr(), y.data_ptr(), 16, None) == G.EWORKSPACE
     assert G.lib.griffin_ff_decode_static(ctypes.byref(L), None, y.data_ptr(), 1, None) == G.EINVAL
     assert G.lib.griffin_ff_decode_static(ctypes.byref(L), x.data_ptr(), y.data_ptr(), 0, None) == G.OK
+
+
+def test_decode_static_replays_in_a_hip_graph():
+    """What the entry point is for: three decode calls recorded into a HIP graph (after one eager call on the
+    device, which looks the array's address up) and replayed with new inputs, eager work and synchronisations
+    between the replays; every replay must give the eager result bit for bit."""
+    dtype, act, d, n, T = synth.DT_BF16, synth.ACT_SILU, 2048, 700, 3
+    c = synth.small_case(405, d, n, 4, dtype, T=3 * T)
+    L, _ = dev_layer(c["Wg"], c["W1"], c["W2"], act, dtype)
+    xs = to_dev(c["xt"], dtype)                               # three sets of T inputs
+    x_buf = torch.empty((T, d), dtype=xs.dtype, device="cuda")
+    y_buf = torch.empty((T, d), dtype=xs.dtype, device="cuda")
+    x_buf.copy_(xs[:T])
+    G.griffin_ff_decode_static(L, x_buf[0], y_buf[0], 1)      # the eager call before any capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for t in range(T):
+                G.griffin_ff_decode_static(L, x_buf[t], y_buf[t], 1)
+    torch.cuda.synchronize()
+    ws = workspace(G.griffin_decode_workspace_bytes(d, n, 1))
+    for rep in range(3):
+        x_buf.copy_(xs[rep * T:(rep + 1) * T])
+        y_buf.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = to_host(y_buf)
+        want = torch.empty_like(y_buf)
+        for t in range(T):                                    # eager, through the entry point with a workspace
+            G.griffin_ff_decode(L, x_buf[t], want[t], 1, workspace=ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(got, to_host(want)), rep
+        ref = oracle.ff_decode(c["xt"][rep * T], c["Wg"], c["W1"], c["W2"], act)
+        assert max_rel(got[0], ref) <= 2e-2
