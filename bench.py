@@ -10,7 +10,7 @@ copies of the compact weights (>= 1 GiB) that the 256 MB Infinity Cache cannot s
 Prints ONE JSON line: whole-job generated tokens/s (`value`), the roofline of the dominant
 kernel (the weight-streaming decode kernel, HBM-bound) and the CPU oracle timed on a bounded
 sample of the same workload.  The default workload is config 3 (the Llama-2-13B-shaped stack of 40
-layers, the model of the paper's latency table); configs 1 and 2 ride along as short extra runs.
+layers, the model of the paper's latency table); configs 1 and 2 ride along as short extra runs (five steps each).
 """
 from __future__ import annotations
 
@@ -287,7 +287,7 @@ def main():
         import copy
         for cid in (1, 2):
             a = copy.copy(args)
-            a.steps, a.warmup, a.config = 3, 1, cid
+            a.steps, a.warmup, a.config = 5, 2, cid
             torch.cuda.empty_cache()
             o = run_single(a, synth.CONFIGS[cid], torch, np, G, synth, hip, brief=True)
             out["config%d" % cid] = {
