@@ -252,11 +252,7 @@ __device__ __forceinline__ void decode_body(const DecodeParams &p, const void *W
 #pragma unroll
             for (int e = 0; e < E; e += 4) {
                 const f32x4 v = {ya[nb][e], ya[nb][e + 1], ya[nb][e + 2], ya[nb][e + 3]};
-#ifdef DEC_PLAIN_STORE
-                *(f32x4 *)(out + (int64_t)((e / 4) * nch + c) * 4) = v;
-#else
                 __builtin_nontemporal_store(v, (f32x4 *)(out + (int64_t)((e / 4) * nch + c) * 4));
-#endif
             }
         }
     }
@@ -296,9 +292,6 @@ __global__ __launch_bounds__(RED_WAVES * 64) void ff_decode_reduce_kernel(const 
                                                                            void *y)
 {
     __shared__ float4 fold[RED_WAVES][RED_Q];
-#ifdef DEC_RED_EMPTY
-    if (P > 0) return;
-#endif
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int b = blockIdx.y;
     const int r = lane >> 3, qi = lane & 7;
@@ -312,11 +305,7 @@ __global__ __launch_bounds__(RED_WAVES * 64) void ff_decode_reduce_kernel(const 
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int pp = p0 + 64 * i;
-#ifdef DEC_PLAIN_LOAD
-            const f32x4 v = pp < P ? *(const f32x4 *)(base + (int64_t)pp * d) : (f32x4){0.f, 0.f, 0.f, 0.f};
-#else
             const f32x4 v = pp < P ? __builtin_nontemporal_load((const f32x4 *)(base + (int64_t)pp * d)) : (f32x4){0.f, 0.f, 0.f, 0.f};
-#endif
             t[i] = make_float4(v.x, v.y, v.z, v.w);
         }
 #pragma unroll
