@@ -179,7 +179,8 @@ int griffin_compact(const griffin_layer *L, const int32_t *idx, int32_t k,
  * for `batch` independent rows x[b] through the ONE block C (a compact block, or a full one
  * with n = D_FF, which is Eq. 1).  x, y: [batch][d] contiguous, C->dtype.  With batch > 1 the
  * rows share one selected set (Section 5.3, Eq. 7) and the weights are streamed once per
- * four rows.
+ * four rows; five rows and more of a bf16 block with d a multiple of 512 up to 5120 take the
+ * matrix cores and stream them once per sixteen rows.
  * workspace >= griffin_decode_workspace_bytes(d, n, batch) bytes, 256-byte aligned.
  */
 size_t griffin_decode_workspace_bytes(int32_t d, int32_t n, int32_t batch);
@@ -284,7 +285,7 @@ int griffin_prompt_phase(const griffin_layer *L, const void *W2p, int64_t ldw, c
 /*
  * MEASUREMENT ONLY -- not part of the method's interface and the one entry point that keeps state
  * between calls (a one-shot, per-thread note of three event handles; every other entry point is
- * stateless).  It exists so that a benchmark can time the kernels of a decode call on the stream
+ * stateless, apart from addresses and kernel attributes looked up once per device).  It exists so that a benchmark can time the kernels of a decode call on the stream
  * they run on (the generation phase is where the time goes, Section 5.2):
  * the next griffin_ff_decode* call made by this thread records, on that call's stream,
  * event_begin just before its weight-streaming kernel, event_mid between that kernel and the
