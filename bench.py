@@ -219,6 +219,11 @@ def run_batched(args, cfg, torch, np, G, synth, hip):
     # the masked pass reads the whole block once per layer-step, the B rows of x, and writes B rows of y
     alg_bytes = 3 * F * d * w + 2 * B * d * w
     achieved = alg_bytes / (avg_us * 1e-6) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as fh:
+            traffic = json.load(fh).get("config%d_k%d" % (cfg.cid, k))
     out = {
         "metric": "pruned-FF decode tokens/s + achieved HBM GB/s; select \u00b5s/layer (prefill)",
         "value": args.steps * T * B / wall,
@@ -237,7 +242,10 @@ def run_batched(args, cfg, torch, np, G, synth, hip):
         "roofline": {
             "bound": "hbm", "kernel": "masked pass: ff_batch_gu_kernel + ff_batch_down_kernel",
             "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None, "algorithmic_bytes_per_launch": alg_bytes,
+            "traffic": traffic,
+            "traffic_source": None if traffic is None else "profiles/traffic.json: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this command on "
+                              "two layers, both kernels of the pass, scaled by the same counters on a copy kernel of known size (stored, not re-measured in this run)",
+            "algorithmic_bytes_per_launch": alg_bytes,
             "avg_kernel_us": avg_us, "median_kernel_us": kern_us[len(kern_us) // 2], "launches_timed": len(kern_us),
             "event_cost_us": event_overhead_us, "unprobed_us_per_layer_step": u,
         },

@@ -336,6 +336,13 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
     // walks through its tiles itself, so that the first loads of the next tile can go out before
     // the epilogue of this one (a workgroup per tile leaves the CU idle while the next one starts).
     const int ntile = p.mt * p.nt, nblk = ntile * p.splits;
+    // Order of the tiles: panels of PANEL_M token tiles; inside a panel the token tile runs fastest, then the
+    // neuron tile.  The 32 workgroups of an XCD then work on 8 token tiles x 4 neuron tiles at any time (12
+    // operand slices stream through its L2 per k-tile) instead of 32 token tiles x 1 neuron tile (33 slices)
+    // when the prompt batch is long; a last panel of fewer token tiles is walked the same way.  With at most
+    // PANEL_M token tiles this is the plain order "token tile fastest".
+    constexpr int PANEL_M = 8;
+    const int full_m = (p.mt / PANEL_M) * PANEL_M, full_tiles = full_m * p.nt;
     const int per_xcd = (nblk + 7) / 8;
     const int wg_per_xcd = gridDim.x >> 3;
     int slot = blockIdx.x >> 3;
@@ -355,8 +362,13 @@ __global__ __launch_bounds__(G_THREADS) void ff1_bf16_mfma_kernel(Ff1Params p)
 #define FF1_TILE_ADDR(logical_)                                                                          \
     {                                                                                                    \
         const int split_ = (logical_) / ntile, tile_ = (logical_) % ntile;                               \
-        tile_n = tile_ / p.mt;                                                                           \
-        m0 = (tile_ % p.mt) * BM;                                                                        \
+        {                                                                                                \
+            const int in_full_ = tile_ < full_tiles ? 1 : 0;                                             \
+            const int w_ = in_full_ ? tile_ % (PANEL_M * p.nt) : tile_ - full_tiles;                     \
+            const int pm_ = in_full_ ? PANEL_M : p.mt - full_m;                                          \
+            tile_n = w_ / pm_;                                                                           \
+            m0 = ((in_full_ ? (tile_ / (PANEL_M * p.nt)) * PANEL_M : full_m) + w_ % pm_) * BM;           \
+        }                                                                                                \
         n0 = tile_n * TILE_N;                                                                            \
         Zt = PLAIN ? p.Z + (int64_t)split_ * p.M * p.ldz : p.Z;                                          \
         _Pragma("unroll") for (int q = 0; q < XQ; ++q)                                                   \

@@ -367,6 +367,10 @@ WALK_CASES = [
     (synth.DT_BF16, 64, 40000, [128], 20000, synth.ACT_SILU, True, True),          # 128-token tiles with biases: 313
     (synth.DT_BF16, 64, 66000, [90], 30000, synth.ACT_RELU, False, False),         # Eq. 2, 128-token tiles, 516 narrow tiles
     (synth.DT_BF16, 64, 128000, [70], 50000, synth.ACT_SILU, False, True),         # Eq. 2, 128-token tiles, 500 wide tiles
+    # more than eight token tiles: the tiles are walked in panels of eight token tiles, the last panel narrower
+    (synth.DT_BF16, 64, 4000, [1500, 1190], 2000, synth.ACT_SILU, True, False),    # 11 x 32 = 352 tiles: one panel of 8, one of 3, ragged both ways
+    (synth.DT_BF16, 64, 2100, [4100], 1000, synth.ACT_GELU_TANH, True, True),      # 17 x 17 = 289 tiles: two panels of 8, one of 1
+    (synth.DT_BF16, 64, 2500, [2560], 1200, synth.ACT_RELU, False, True),          # Eq. 2, wide tiles: 10 x 10 = 100 tiles, panels of 8 and 2, no walk
 ]
 
 
