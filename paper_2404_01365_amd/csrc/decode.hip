@@ -48,6 +48,8 @@ struct MultiPtrs {
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+// cache-policy bits of a raw buffer store on gfx942/gfx950: sc0 (bit 0) and sc1 (bit 4) = write through to memory
+[[maybe_unused]] constexpr int DEC_AUX_WRITE_THROUGH = 1 | 16;
 
 // by value on purpose: bit-casting a vector element expression (v.y) in place picks element 0
 __device__ __forceinline__ bf16x2 as_bf16x2(uint32_t v) { return __builtin_bit_cast(bf16x2, v); }
@@ -246,14 +248,21 @@ __device__ __forceinline__ void decode_body(const DecodeParams &p, const void *W
         // The partial row is private to this kernel and the one that adds the rows up, so its columns are
         // stored in the order that makes every store instruction one contiguous kilobyte: quad e/4 of
         // chunk c goes to float4 slot (e/4) * nch + c (a lane's 8 columns would otherwise leave as two
-        // instructions that each fill every other 16 bytes).
+        // instructions that each fill every other 16 bytes).  The stores are write-through (sc0 sc1): the rows
+        // then sit in memory when the kernel ends instead of as dirty lines in eight L2s that the end of the
+        // kernel has to write back before the adding kernel may start (0.4 us per layer-token less than with
+        // plain or non-temporal stores, measured on three shapes).
         if (team == 0 && valid && b + nb < p.batch) {
+#if defined(__HIP_DEVICE_COMPILE__)      // the host pass has no buffer builtins
             float *out = p.part + ((int64_t)(b + nb) * p.P + blockIdx.x) * d;
+            const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc((void *)out, 0, 0x7FFFFFFE, 0x00020000);
 #pragma unroll
             for (int e = 0; e < E; e += 4) {
                 const f32x4 v = {ya[nb][e], ya[nb][e + 1], ya[nb][e + 2], ya[nb][e + 3]};
-                __builtin_nontemporal_store(v, (f32x4 *)(out + (int64_t)((e / 4) * nch + c) * 4));
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rp, ((e / 4) * nch + c) * 16, 0,
+                                                       DEC_AUX_WRITE_THROUGH);
             }
+#endif
         }
     }
 }
