@@ -37,6 +37,7 @@ struct Ff1Params {
     int64_t ldx, ldw, ldz, ldzb;
     int32_t M, F, d, nt, mt;
     int32_t splits, kt_per_split;    // ranges of the contraction (1 for the activations) and 64-wide k-tiles per range
+    int32_t z_stream;                // Z leaves with the non-temporal hint (see launch_ff1)
 };
 
 // Epilogue shared by the MFMA kernels: sigma, gating, store of Z, row sums of z^2.
@@ -137,6 +138,11 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
         // each.  Every LDS access here is inline asm: the next tile's first LDS-DMA loads are in
         // flight, and an access the compiler knows about would wait for them (and for the Z stores).
         const uint32_t patch = patch_lds + (uint32_t)(wave * 32 * 256);
+#if defined(__HIP_DEVICE_COMPILE__)
+        // the tile's rows of Z as a raw buffer (byte offsets inside a tile stay below 2^31: 256 rows of at most 2^20 floats;
+        // cache-policy bit 1 = non-temporal)
+        const __amdgpu_buffer_rsrc_t zrsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(p.Z + (int64_t)m0 * p.ldz), 0, 0x7FFFFFFE, 0x00020000);
+#endif
         const uint32_t wr = patch + (uint32_t)(l31 * 256);
         const int rrow = lane >> 4, rch = lane & 15;
         // biases of this lane's 32 columns (four consecutive ones per register pair), fetched before any store
@@ -201,12 +207,20 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
                 const int row = 4 * j + rrow;
                 asm volatile("ds_read_b128 %0, %1" : "=v"(pv[j]) : "v"(patch + (uint32_t)(row * 256 + ((rch ^ (row & 15)) * 16))) : "memory");
             }
+#if defined(__HIP_DEVICE_COMPILE__)      /* the host pass has no buffer builtins */
+#define FF1_Z_STREAM_STORE(v_, elem_) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v_), zrsrc, (elem_) * 4, 0, 2)
+#else
+#define FF1_Z_STREAM_STORE(v_, elem_) (void)0
+#endif
 #define FF1_PATCH_STORE(j_)                                                                          \
             {                                                                                        \
                 asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(pv[j_]) : "n"(7 - (j_)) : "memory");     \
                 const int tok = tok0 + 4 * (j_);                                                     \
                 if (tok < p.M && ncol < p.F) {                                                       \
-                    *(f32x4_t *)(p.Z + (int64_t)tok * p.ldz + ncol) = pv[j_];                        \
+                    if (p.z_stream)      /* a buffer store: the two flavours must stay two instructions */ \
+                        FF1_Z_STREAM_STORE(pv[j_], (tok - m0) * (int)p.ldz + ncol);                  \
+                    else                                                                             \
+                        *(f32x4_t *)(p.Z + (int64_t)tok * p.ldz + ncol) = pv[j_];                    \
                     if (EXTRA && !PLAIN && p.Zb) {                                                   \
                         uint2 h_;                                                                    \
                         h_.x = f32_to_bf16_bits(pv[j_][0]) | (f32_to_bf16_bits(pv[j_][1]) << 16);    \
@@ -219,6 +233,7 @@ __device__ __forceinline__ bool ff1_mfma_epilogue_t(const Ff1Params &p, f32x16 (
             FF1_PATCH_STORE(0) FF1_PATCH_STORE(1) FF1_PATCH_STORE(2) FF1_PATCH_STORE(3)
             FF1_PATCH_STORE(4) FF1_PATCH_STORE(5) FF1_PATCH_STORE(6) FF1_PATCH_STORE(7)
 #undef FF1_PATCH_STORE
+#undef FF1_Z_STREAM_STORE
         }
             if (!PLAIN)     // the row's sum of squares over all the columns of the tile (both halves)
                 asm volatile("ds_write_b32 %0, %1" :: "v"(rs_lds + (uint32_t)(((wn * 2 + lh) * BM + lrow) * 4)), "v"(sq) : "memory");
@@ -899,6 +914,11 @@ int launch_ff1(const griffin_layer &L, const void *X, int64_t ldx, int64_t M, fl
     p.ldx = ldx; p.ldw = L.ld; p.ldz = ldz;
     p.M = (int32_t)M; p.F = L.n; p.d = L.d;
     p.splits = 1; p.kt_per_split = L.d / 64;
+    // Z is read again at once by the statistic kernel.  While it fits the 256 MB Infinity Cache, plain stores leave it
+    // there for that kernel; a Z several times that size is better sent past the caches (measured, statistic kernel
+    // after plain / non-temporal stores: 201 MB of Z 38.3 / 44.6 us, 57 MB 14.5 / 16.4 us, 1.18 GB 284 / 243 us; the
+    // product itself takes the same time either way).
+    p.z_stream = ((int64_t)M * L.n * 4 > ((int64_t)384 << 20) && ldz <= (1 << 20)) ? 1 : 0;   // (32-bit byte offsets inside a tile)
     p.nt = ff1_ntiles(L);
     const bool gated = L.Wg != nullptr;
     // An Eq. 2 block on the direct-to-LDS kernel takes 256-column tiles (one row-sum partial per tile) when that
@@ -981,6 +1001,7 @@ int launch_gemm_nt_partials(const void *A, int64_t lda, const void *B, int64_t l
     p.ldx = lda; p.ldw = ldb; p.ldz = N;
     p.M = (int32_t)M; p.F = N; p.d = K;
     p.splits = splits; p.kt_per_split = kt_per_split;
+    p.z_stream = 0;
     p.nt = (N + 2 * G_BN - 1) / (2 * G_BN);        // 256-column tiles: both sets of accumulators hold columns of B
     if (M > 128) {
         p.mt = (int32_t)((M + 255) / 256);
