@@ -371,6 +371,8 @@ WALK_CASES = [
     (synth.DT_BF16, 64, 4000, [1500, 1190], 2000, synth.ACT_SILU, True, False),    # 11 x 32 = 352 tiles: one panel of 8, one of 3, ragged both ways
     (synth.DT_BF16, 64, 2100, [4100], 1000, synth.ACT_GELU_TANH, True, True),      # 17 x 17 = 289 tiles: two panels of 8, one of 1
     (synth.DT_BF16, 64, 2500, [2560], 1200, synth.ACT_RELU, False, True),          # Eq. 2, wide tiles: 10 x 10 = 100 tiles, panels of 8 and 2, no walk
+    # Z of 406 MB, more than the product keeps in the caches: it leaves through the streaming stores (24 x 130 tiles)
+    (synth.DT_BF16, 64, 16640, [3100, 3000], 8000, synth.ACT_SILU, True, False),
 ]
 
 
